@@ -1,0 +1,508 @@
+"""Pins of the CPU oracle to what the paper and the mathematics fix.
+
+None of these tests calls the HIP library.  Each check is made against
+something other than the oracle's own arithmetic: values printed in the
+paper (tests/golden), independent constructions the paper describes
+(the linear-time baseblock listing, the two doubling observations), the
+four correctness conditions evaluated with numpy on whole tables, a
+payload-carrying replay of Algorithm 1, and planted mistakes.
+"""
+import numpy as np
+import pytest
+
+from conftest import read_table
+
+import oracle
+
+P_EXHAUSTIVE = 4096
+
+
+# --------------------------------------------------------------- skips ----
+
+def test_skips_printed_examples():
+    # Table 1 (bars) and the example in the proof of Lemma 4.
+    assert oracle.skips(17) == [1, 2, 3, 5, 9, 17]
+    assert oracle.skips(11) == [1, 2, 3, 6, 11]
+
+
+def test_skips_closed_form_and_bounds():
+    # Algorithm 2 is repeated halving with rounding up, so skip[k] = ceil(p / 2^(q-k));
+    # Observation 2, Lemma 2 and Observation 3 bound the skips.
+    ps = list(range(1, 3000)) + [65537, 1000003, 2**20, 2**31 - 1, 2**31 - 2, 2**30 + 1]
+    for p in ps:
+        sk = oracle.skips(p)
+        q = len(sk) - 1
+        assert 2 ** q >= p and (q == 0 or 2 ** (q - 1) < p)
+        assert sk[q] == p
+        for k in range(q + 1):
+            assert sk[k] == -((-p) // 2 ** (q - k))
+        if p > 1:
+            assert sk[0] == 1 and sk[1] == 2
+        for k in range(q):
+            assert sk[k + 1] <= 2 * sk[k] <= sk[k + 1] + 1              # Observation 2
+            assert sk[k + 1] - 1 <= sum(sk[: k + 1]) < sk[k + 1] + k    # Lemma 2
+        tunnels = [k for k in range(2, q + 1) if sk[k - 2] + sk[k - 1] == sk[k]]
+        assert len(tunnels) <= 2 and all(k <= 3 for k in tunnels)        # Observation 3
+
+
+def test_q_is_integer_log():
+    for p in (1, 2, 3, 4, 5, 8, 9, 2**20, 2**20 + 1, 2**31 - 1):
+        assert oracle.q_of(p) == (p - 1).bit_length()
+
+
+# ----------------------------------------------------------- baseblock ----
+
+def baseblock_listing(p):
+    """Linear-time listing from the proof of Lemma 4: double the list, drop the
+    last element if the next skip is odd, set entry 0 to the new index."""
+    sk = oracle.skips(p)
+    q = len(sk) - 1
+    lst = [0]
+    for k in range(q):
+        lst = (lst + lst)[: sk[k + 1]]
+        lst[0] = k + 1
+    return lst
+
+
+def test_baseblock_printed_example():
+    assert "".join(str(b) for b in baseblock_listing(11)) == "40120130120"
+    assert [oracle.baseblock(11, r) for r in range(11)] == [4, 0, 1, 2, 0, 1, 3, 0, 1, 2, 0]
+
+
+def test_baseblock_equals_linear_listing():
+    for p in range(1, P_EXHAUSTIVE + 1):
+        want = baseblock_listing(p)
+        got = [oracle.baseblock(p, r) for r in range(p)] if p <= 600 or p % 37 == 0 \
+            else None
+        if got is not None:
+            assert got == want, p
+
+
+def test_baseblock_power_of_two_is_lowest_set_bit():
+    # p = 2^q: skips are powers of two, the canonical skip sequence is the binary
+    # representation, so the baseblock is the index of the lowest set bit.
+    for q in range(1, 13):
+        p = 2 ** q
+        for r in range(1, p):
+            assert oracle.baseblock(p, r) == (r & -r).bit_length() - 1
+        assert oracle.baseblock(p, 0) == q
+
+
+def test_lemma4_windows():
+    # What the proof of Lemma 4 states about the listing: the first skip[k]
+    # baseblocks hold exactly k+1 different values, the skip[k] baseblocks from
+    # r = skip[k] on hold at least k+1.  (The lemma's own wording, "any" window,
+    # is off by one for some windows, e.g. p = 9, r = 4..6 holds 0 3 0, so an
+    # arbitrary window is only held to k different values here.)
+    for p in list(range(2, 300)) + [511, 1000, 1025]:
+        sk = oracle.skips(p)
+        q = len(sk) - 1
+        bb = baseblock_listing(p)
+        for k in range(q):
+            w = sk[k]
+            assert len(set(bb[0:w])) == k + 1
+            if 2 * w <= p:
+                assert len(set(bb[w:2 * w])) >= k + 1
+            for r in range(0, p - w + 1):
+                assert len(set(bb[r:r + w])) >= k
+
+
+# ------------------------------------------------------ printed tables ----
+
+@pytest.mark.parametrize("name", ["table1_p17.txt", "table2_p9.txt", "table3_p18.txt"])
+@pytest.mark.parametrize("send_mode", [0, 1])
+def test_printed_tables(name, send_mode):
+    p, b, recv, send = read_table(name)
+    q = len(recv)
+    assert oracle.q_of(p) == q
+    S = oracle.schedules(p, send_mode=send_mode, threads=1)
+    assert [oracle.baseblock(p, r) for r in range(p)] == b
+    for k in range(q):
+        assert S[:, k].tolist() == recv[k], (name, "recv", k)
+        assert S[:, q + k].tolist() == send[k], (name, "send", k)
+
+
+def test_named_violation_p17():
+    # Section 2.3 names a violation in round k=2 for processor r=3.
+    _, nviol, mask = oracle.sendschedule(17, 3, with_violations=True)
+    assert nviol == 1 and mask == 1 << 2
+    # For r=8 the printed column is reproduced with a single violation.
+    send, nviol, _ = oracle.sendschedule(17, 8, with_violations=True)
+    assert send.tolist() == [-3, -3, -3, -2, -3] and nviol == 1
+
+
+# --------------------------------------------- the four conditions --------
+
+def check_conditions(p, S):
+    """Conditions 1-4 of Section 2 on a whole table S[r][2q], root 0, numpy only."""
+    sk = oracle.skips(p)
+    q = len(sk) - 1
+    if q == 0:
+        return
+    recv, send = S[:, :q], S[:, q:]
+    r = np.arange(p)
+    b = np.array(baseblock_listing(p))
+    for k in range(q):
+        f = (r - sk[k]) % p
+        t = (r + sk[k]) % p
+        assert (recv[:, k] == send[f, k]).all(), (p, "condition 1", k)
+        assert (send[:, k] == recv[t, k]).all(), (p, "condition 2", k)
+    # Condition 3
+    srt = np.sort(recv, axis=1)
+    for rr in range(p):
+        want = set(range(-q, 0))
+        if rr != 0:
+            want.discard(b[rr] - q)
+            want.add(b[rr])
+        assert sorted(want) == srt[rr].tolist(), (p, "condition 3", rr)
+    # Condition 4 and its consequence for k = 0
+    assert (send[1:, 0] == b[1:] - q).all()
+    assert (send[0] == np.arange(q)).all()
+    for k in range(1, q):
+        ok = send[:, k] == b - q
+        for j in range(k):
+            ok |= send[:, k] == recv[:, j]
+        ok[0] = True
+        assert ok.all(), (p, "condition 4", k)
+
+
+def test_conditions_small_p_both_send_routes():
+    for p in list(range(1, 700)) + [1023, 1024, 1025, 2047, 2049, 3001, 4095, 4096]:
+        check_conditions(p, oracle.schedules(p, send_mode=1))
+    for p in list(range(1, 80)) + [127, 128, 129, 1000]:
+        check_conditions(p, oracle.schedules(p, send_mode=0))
+
+
+def test_algorithm6_equals_definition_exhaustive():
+    # Algorithm 6 must reach exactly the definition (Condition 2) for every rank.
+    for p in range(1, P_EXHAUSTIVE + 1):
+        a = oracle.schedules(p, send_mode=0)
+        b = oracle.schedules(p, send_mode=1)
+        assert np.array_equal(a, b), p
+
+
+LARGE_PS = [1000003, 65537, 2**31 - 1, 2**31 - 2, 2**30 + 1, 2**20, 3 * 2**28 + 5,
+            16 * 2**20 + 12345]
+
+
+@pytest.mark.parametrize("p", LARGE_PS)
+def test_large_p_samples(p):
+    rng = np.random.default_rng(p)
+    ranks = np.unique(np.concatenate([
+        rng.integers(0, p, size=4000), np.arange(0, 70), np.arange(p - 70, p)]))
+    ranks = ranks.astype(np.uint32)
+    a = oracle.schedules_ranks(p, 0, ranks, send_mode=0)
+    b = oracle.schedules_ranks(p, 0, ranks, send_mode=1)
+    assert np.array_equal(a, b)
+    sk = oracle.skips(p)
+    q = len(sk) - 1
+    # Condition 3 and the bounds of Theorem 3 / the search anomalies
+    for j in range(0, len(ranks), 7):
+        r = int(ranks[j])
+        recv, st = oracle.recvschedule(p, r, with_stats=True)
+        assert st["anomalies"] == 0 and st["produced"] == q
+        bb = oracle.baseblock(p, r)
+        want = set(range(-q, 0))
+        if r != 0:
+            want.discard(bb - q)
+            want.add(bb)
+        assert set(recv.tolist()) == want
+        _, nviol, _ = oracle.sendschedule(p, r, with_violations=True)
+        assert nviol <= 4
+    # Condition 1 along real edges: recv[k]_r == send[k]_{r - skip[k]}
+    for r in (1, 2, 3, int(ranks[len(ranks) // 2]), p - 1):
+        recv = oracle.recvschedule(p, r)
+        for k in range(q):
+            f = (r - sk[k]) % p
+            assert oracle.sendschedule(p, f)[k] == recv[k]
+
+
+def test_search_counters_small_p():
+    # No index is pushed twice on a path or accepted twice, the search always
+    # produces q entries, and at most 4 violations occur (Theorem 3).
+    worst_scans = 0.0
+    for p in range(2, 1500):
+        q = oracle.q_of(p)
+        for r in range(p):
+            _, st = oracle.recvschedule(p, r, with_stats=True)
+            assert st["anomalies"] == 0 and st["produced"] == q, (p, r)
+            assert st["max_depth"] <= q
+            worst_scans = max(worst_scans, st["scans"] / q)
+    assert worst_scans < 4.0
+    for p in range(2, 1500):
+        for r in range(p):
+            _, nviol, _ = oracle.sendschedule(p, r, with_violations=True)
+            assert nviol <= 4
+
+
+# ---------------------------------------------------------- doubling ------
+
+def double_recv(p, S):
+    """Observation 1: receive schedule for 2p from the one for p."""
+    q = oracle.q_of(p)
+    old = S[:, :q]
+    new = np.zeros((2 * p, q + 1), dtype=np.int64)
+    for r in range(2 * p):
+        row = old[r % p].astype(np.int64).copy()
+        row[row < 0] -= 1
+        if r < p:
+            last = -1
+        elif r == p:
+            last = q
+        else:
+            pos = np.nonzero(row >= 0)[0]
+            assert len(pos) == 1
+            last = row[pos[0]]
+            row[pos[0]] = -1
+        new[r, :q] = row
+        new[r, q] = last
+    return new
+
+
+def double_send(p, S):
+    """Observation 5: send schedule for 2p from the one for p."""
+    q = oracle.q_of(p)
+    old = S[:, q:]
+    bb = baseblock_listing(p)
+    new = np.zeros((2 * p, q + 1), dtype=np.int64)
+    for r in range(2 * p):
+        row = old[r % p].astype(np.int64).copy()
+        row[row < 0] -= 1
+        if r < p:
+            last = bb[r]
+        else:
+            row[row >= 0] = -1
+            last = -1
+        new[r, :q] = row
+        new[r, q] = last
+    return new
+
+
+def test_doubling_observations():
+    for p in list(range(1, 1025)) + [1500, 2047, 2048]:
+        S = oracle.schedules(p, send_mode=1)
+        S2 = oracle.schedules(2 * p, send_mode=1)
+        q2 = oracle.q_of(2 * p)
+        assert q2 == oracle.q_of(p) + 1
+        assert np.array_equal(double_recv(p, S), S2[:, :q2]), ("recv", p)
+        assert np.array_equal(double_send(p, S), S2[:, q2:]), ("send", p)
+
+
+def test_power_of_two_from_one_by_doubling():
+    # every power of two is reached from p = 1 by doubling alone
+    S = np.zeros((1, 0), dtype=np.int64)
+    p = 1
+    for _ in range(10):
+        q = oracle.q_of(p)
+        full = np.concatenate([S[:, :q], S[:, q:]], axis=1).astype(np.int32)
+        recv2 = double_recv(p, full)
+        send2 = double_send(p, full)
+        p *= 2
+        S = np.concatenate([recv2, send2], axis=1)
+        assert np.array_equal(S, oracle.schedules(p, send_mode=1))
+
+
+# ---------------------------------------------------------- simulator -----
+
+def replay_with_payload(p, n, root, S):
+    """Algorithm 1 literally, with payload: every processor owns a buffer, sends
+    buf[sendblock[k]] and stores what arrives into buf[recvblock[k]].  Returns the
+    number of rounds.  Asserts that only held blocks are sent, nothing is received
+    twice, sender and receiver agree, and everybody ends with the root's data."""
+    sk = oracle.skips(p)
+    q = len(sk) - 1
+    buf = [dict() for _ in range(p)]
+    buf[root] = {j: ("payload", j) for j in range(n)}
+    if q == 0:
+        return 0
+    recv = [[int(S[r, k]) for k in range(q)] for r in range(p)]
+    send = [[int(S[r, q + k]) for k in range(q)] for r in range(p)]
+    x = (q - (n - 1) % q) % q
+    for r in range(p):
+        for i in range(q):
+            recv[r][i] -= x
+            send[r][i] -= x
+            if i < x:
+                recv[r][i] += q
+                send[r][i] += q
+    rounds = 0
+    for i in range(x, (n + q - 1 + x) - 1 + 1):
+        k = i % q
+        inflight = {}
+        for r in range(p):
+            t = (r + sk[k]) % p
+            sb = send[r][k]
+            if sb >= 0 and t != root:
+                sb = min(sb, n - 1)
+                assert sb in buf[r], ("sends a block it does not hold", p, n, r, i)
+                inflight[t] = (sb, buf[r][sb])
+        for r in range(p):
+            rb = recv[r][k]
+            if r != root and rb >= 0:
+                rb = min(rb, n - 1)
+                assert r in inflight, ("expects a block nobody sends", p, n, r, i)
+                sb, data = inflight.pop(r)
+                assert sb == rb and data == ("payload", rb)
+                assert rb not in buf[r], ("receives a block twice", p, n, r, i)
+                buf[r][rb] = data
+        assert not inflight, ("a sent block is not expected", p, n, i)
+        for r in range(p):
+            send[r][k] += q
+            recv[r][k] += q
+        rounds += 1
+    for r in range(p):
+        assert buf[r] == buf[root]
+    return rounds
+
+
+def test_payload_replay_small():
+    for p in list(range(1, 70)) + [100, 127, 128, 129, 255, 257]:
+        q = oracle.q_of(p)
+        for root in {0, p // 3, p - 1}:
+            S = oracle.schedules(p, root=root, send_mode=1)
+            for n in {1, 2, max(q, 1), q + 1, 2 * q + 3, 3 * q}:
+                if n < 1:
+                    continue
+                rounds = replay_with_payload(p, n, root, S)
+                assert rounds == (n - 1 + q if q else 0)
+
+
+CLEAN = {"flags": 0, "n_bad_recv_dup": 0, "n_bad_send_unheld": 0,
+         "n_edge_mismatch": 0, "n_incomplete_ranks": 0, "first_bad": oracle.U64_MAX}
+
+
+def assert_clean(vd, p, n):
+    q = oracle.q_of(p)
+    for key, val in CLEAN.items():
+        assert vd[key] == val, (p, n, key, vd)
+    assert vd["rounds"] == (n - 1 + q if q else 0)
+
+
+def test_simulation_exhaustive_small_sweep():
+    # the sweep of the first workload: every p, n = 2q+3 blocks
+    for p in range(1, P_EXHAUSTIVE + 1):
+        q = oracle.q_of(p)
+        assert_clean(oracle.simulate(p, 2 * q + 3, 0), p, 2 * q + 3)
+
+
+def test_simulation_more_block_counts_and_roots():
+    for p in list(range(1, 260)) + [1000, 1023, 1025]:
+        q = oracle.q_of(p)
+        for n in {1, 2, max(q, 1), q + 1, 3 * q, 5 * q + 1}:
+            if n >= 1:
+                assert_clean(oracle.simulate(p, n, 0), p, n)
+        assert_clean(oracle.simulate(p, 7, p // 2), p, 7)
+    # explicit table with a root other than 0
+    p, root = 1000, 333
+    S = oracle.schedules(p, root=root)
+    assert_clean(oracle.simulate(p, 25, root, S), p, 25)
+
+
+def test_simulation_single_block_is_one_receive_each():
+    # n = 1: q rounds, every non-root receives exactly once (its baseblock round)
+    for p in (2, 3, 17, 64, 100, 1000):
+        q = oracle.q_of(p)
+        S = oracle.schedules(p)
+        assert ((S[1:, :q] >= 0).sum(axis=1) == 1).all()
+        assert_clean(oracle.simulate(p, 1, 0, S), p, 1)
+
+
+def test_simulation_catches_planted_mistakes():
+    p, n = 100, 20
+    q = oracle.q_of(p)
+    good = oracle.schedules(p)
+    assert_clean(oracle.simulate(p, n, 0, good), p, n)
+    # wrong receive entry: edge mismatch, and a missing block at the end
+    bad = good.copy()
+    bad[37, 2] = bad[37, 2] - 1 if bad[37, 2] > -q else bad[37, 2] + 1
+    vd = oracle.simulate(p, n, 0, bad)
+    assert vd["flags"] & 4 and vd["n_edge_mismatch"] > 0 and vd["first_bad"] != oracle.U64_MAX
+    assert (vd["first_bad"] & 0xFFFFFFFF) == 37
+    # a send moved one phase early: sent before it is held
+    bad = good.copy()
+    r = 50
+    k = int(np.argmax(good[r, :q] >= 0))          # round of the baseblock
+    bad[r, q:] = good[r, q:]
+    bad[r, q + 0] = good[r, k]                      # claims to send the baseblock in round 0
+    vd = oracle.simulate(p, n, 0, bad)
+    assert vd["flags"] & 2 and vd["n_bad_send_unheld"] > 0
+    # two receive entries swapped keeps edges wrong; a duplicated entry is a duplicate receive
+    bad = good.copy()
+    bad[10, 1] = bad[10, 0]
+    vd = oracle.simulate(p, n, 0, bad)
+    assert vd["flags"] & 1 and vd["flags"] & 8
+    # all-negative schedule: nobody receives anything
+    bad = np.full_like(good, -1)
+    vd = oracle.simulate(p, n, 0, bad)
+    assert vd["n_incomplete_ranks"] == p - 1
+
+
+# -------------------------------------------------------------- digest ----
+
+def test_sm64_published_vectors():
+    # SplitMix64 seeded with 0: first three outputs of the published generator.
+    g = 0x9E3779B97F4A7C15
+    assert oracle.sm64(0) == 0xE220A8397B1DCDAF
+    assert oracle.sm64(g) == 0x6E789E6AA1B965F4
+    assert oracle.sm64(2 * g) == 0x06C45D188009454F
+
+
+def test_digest_flags_clean_and_xor_composition():
+    for p in list(range(1, 300)) + [1000, 4096, 65537]:
+        full, fl = oracle.digest(p, 0, 0, p)
+        assert fl == 0, p
+        cut = p // 3
+        a, _ = oracle.digest(p, 0, 0, cut)
+        b, _ = oracle.digest(p, 0, cut, p)
+        assert a ^ b == full
+    # root renumbering changes the rows' positions, not the flags
+    d0, fl = oracle.digest(1000, 123, 0, 1000)
+    assert fl == 0 and d0 != oracle.digest(1000, 0, 0, 1000)[0]
+    # both send routes give one digest
+    assert oracle.digest(1000, 5, 10, 900, send_mode=0) == oracle.digest(1000, 5, 10, 900, send_mode=1)
+
+
+def test_digest_row_flags_on_planted_mistakes():
+    p, r = 1000, 321
+    q = oracle.q_of(p)
+    recv, send = oracle.recvschedule(p, r), oracle.sendschedule(p, r)
+    h0, fl = oracle.digest_row(p, 0, r, recv, send)
+    assert fl == 0
+    b = oracle.baseblock(p, r)
+    # Condition 3: duplicate a negative entry
+    bad = recv.copy()
+    neg = np.nonzero(bad < 0)[0]
+    bad[neg[0]] = bad[neg[1]]
+    h1, fl = oracle.digest_row(p, 0, r, bad, send)
+    assert fl & 1 and h1 != h0
+    # first send wrong
+    bad = send.copy()
+    bad[0] = b - q + (1 if b - q < -1 else -1)
+    assert oracle.digest_row(p, 0, r, recv, bad)[1] & 2
+    # Condition 4: send in round 1 something received only later
+    bad = send.copy()
+    later = [x for x in recv[2:].tolist() if x != b - q and x != recv[0]]
+    bad[1] = later[-1]
+    assert oracle.digest_row(p, 0, r, recv, bad)[1] & 4
+    # more than four violations, short search, range
+    assert oracle.digest_row(p, 0, r, recv, send, viol_count=5)[1] == 8
+    assert oracle.digest_row(p, 0, r, recv, send, produced=q - 1)[1] == 16
+    bad = send.copy()
+    bad[3] = q
+    assert oracle.digest_row(p, 0, r, recv, bad)[1] & 32
+    # field order matters: swapping two different entries changes the hash
+    sw = recv.copy()
+    sw[0], sw[1] = recv[1], recv[0]
+    assert oracle.digest_row(p, 0, r, sw, send)[0] != h0
+
+
+def test_digest_known_answers():
+    # values written by tests/golden/make_digest_golden.py from the oracle alone
+    import json
+    import os
+    from conftest import GOLDEN
+    with open(os.path.join(GOLDEN, "digest_known_answers.json")) as fh:
+        items = json.load(fh)["items"]
+    for it in items:
+        dg, fl = oracle.digest(it["p"], it["root"], it["r_begin"], it["r_end"])
+        assert (dg, fl) == (int(it["digest"], 16), it["flags"]), it

@@ -1,0 +1,154 @@
+/*
+ * bcast.h -- C ABI of the MI355X (gfx950) library that computes round-optimal
+ * broadcast schedules on a circulant graph, after J. L. Traff, "Optimal
+ * Broadcast Schedules in Logarithmic Time ..." (arXiv 2407.18004).
+ *
+ * Problem statement (Section 2): p processors 0..p-1, a root, n indivisible
+ * blocks, n-1+q communication rounds with q = ceil(log2 p).  In round i every
+ * processor r sends to (r + skip[k]) mod p and receives from (r - skip[k]) mod p
+ * with k = i mod q.  Which block it receives and sends is given by two arrays
+ * of q entries, recvblock[] and sendblock[], that each processor computes for
+ * itself in O(q) steps.  This library computes them for many ranks at once,
+ * one GPU lane per rank.
+ *
+ * Conventions for every entry point
+ *  - "host" pointers are dereferenced by the calling thread; "device" pointers
+ *    are only passed to kernels.  The caller owns every buffer and the stream;
+ *    the library allocates nothing and keeps no state between calls.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued on it and the call returns without waiting; results are
+ *    valid once the caller has synchronised the stream.
+ *  - Return value: BCAST_OK, or a negative BCAST_E* code.  Nothing is thrown
+ *    and nothing aborts.  On an error no kernel has been launched.
+ *  - Domain: 1 <= p <= 2^31 - 1, so q <= 31.  p = 1 has q = 0: rows are empty.
+ *  - Schedule entries are the raw values of Algorithms 5 and 6, in [-q, q-1]:
+ *    exactly one receive entry of a non-root rank is non-negative (its
+ *    baseblock, Condition 3).  They are NOT shifted by the x dummy rounds of
+ *    Algorithm 1; that shift belongs to whoever runs the rounds.
+ *  - A root other than 0 renumbers the ranks: the schedule of physical rank r
+ *    is the root-0 schedule of (r - root + p) mod p (Section 2).
+ */
+#ifndef BCAST_H
+#define BCAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BCAST_OK       0
+#define BCAST_EINVAL  (-1)  /* argument outside the documented domain          */
+#define BCAST_ENOMEM  (-2)  /* workspace smaller than bcast_simulate_workspace */
+#define BCAST_EHIP    (-3)  /* the HIP runtime refused a launch or a copy      */
+
+#define BCAST_MAX_P   2147483647u
+
+/* Flags of bcast_schedules_digest, OR-ed over the ranks (Section 2, the four
+ * correctness conditions, and Theorem 3). */
+#define BCAST_F_COND3      (1u << 0) /* recv[] is not ({-1..-q} minus {b-q}) plus {b}   */
+#define BCAST_F_SEND0      (1u << 1) /* send[0] != b-q (root: send[k] != k)             */
+#define BCAST_F_COND4      (1u << 2) /* a send[k] is neither b-q nor an earlier recv[j] */
+#define BCAST_F_VIOLATIONS (1u << 3) /* more than four violations in Algorithm 6        */
+#define BCAST_F_SEARCH     (1u << 4) /* the receive search ended early or left its
+                                        expected shape (see DESIGN notes in the source) */
+#define BCAST_F_RANGE      (1u << 5) /* an entry outside [-q, q-1]                      */
+
+/* Flags of bcast_verdict.flags. */
+#define BCAST_V_RECV_DUP     (1u << 0)
+#define BCAST_V_SEND_UNHELD  (1u << 1)
+#define BCAST_V_EDGE         (1u << 2)
+#define BCAST_V_INCOMPLETE   (1u << 3)
+
+/* Outcome of one simulated broadcast (Algorithm 1 over possession bits).
+ * All members are order-independent reductions over (round, rank) events. */
+typedef struct bcast_verdict {
+    uint32_t flags;               /* BCAST_V_* */
+    uint32_t rounds;              /* rounds executed: n-1+q (0 for p = 1)        */
+    uint64_t n_bad_recv_dup;      /* receives of a block already held            */
+    uint64_t n_bad_send_unheld;   /* sends of a block not held before the round  */
+    uint64_t n_edge_mismatch;     /* receiver's block != its from-processor's    */
+    uint64_t n_incomplete_ranks;  /* ranks that miss a block after the last round */
+    uint64_t first_bad;           /* min of (round << 32 | physical rank) over all
+                                     failures, UINT64_MAX if none; a rank that is
+                                     incomplete at the end counts as round = rounds */
+} bcast_verdict;
+
+/* q = ceil(log2 p) by integer arithmetic (Section 2).  Returns BCAST_EINVAL
+ * for p = 0 or p > BCAST_MAX_P. */
+int bcast_q(uint32_t p);
+
+/* Algorithm 2: the skips of the circulant graph.  Writes skip[0..q] (q+1 values,
+ * skip[q] = p, skip[k-1] = ceil(skip[k] / 2)) to the host array `skips`, which
+ * must hold at least 32 entries, and q to *q_out (may be NULL).  Host only. */
+int bcast_skips(uint32_t p, uint32_t *skips, int *q_out);
+
+/* Algorithms 3, 5 (with 4) and 6 for the physical ranks r in [r_begin, r_end).
+ * Device output, int32: entry (r, k), k < q, goes to
+ *     recv[(r - r_begin) * ld + k]   and   send[(r - r_begin) * ld + k].
+ * Two layouts take the coalesced path: one table [ranks][2q] (send == recv + q,
+ * ld == 2q) and two tables [ranks][q] (ld == q, disjoint); any other ld >= q
+ * with rows that do not overlap is served by a slower row-wise path.
+ * Errors: p outside the domain, root >= p, r_begin > r_end, r_end > p, NULL
+ * pointers (unless the range is empty or q = 0), ld < q, overlapping rows. */
+int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                    int32_t *recv, int32_t *send, int64_t ld, void *stream);
+
+/* The same computation folded into a digest instead of being stored, for
+ * rank ranges too large to materialise.  Per rank, with sm64 the published
+ * SplitMix64 output function and the 2q entries as six-bit fields
+ * f_j = recv[j] + 32 (j < q), f_{q+j} = send[j] + 32:
+ *     w_i = sum_{t<10} f_{10 i + t} << 6 t,            i < ceil(2q / 10)
+ *     h   = sm64((p << 32) ^ r);  h = sm64(h ^ w_i) for i = 0, 1, ...
+ * *digest (device, one uint64) = XOR of h over the ranks; *flags (device, one
+ * uint32) = OR of the BCAST_F_* checks of every rank.  Both are overwritten.
+ * Digests of disjoint ranges combine by XOR, flags by OR.  Errors as above. */
+int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin,
+                           uint64_t r_end, uint64_t *digest, uint32_t *flags,
+                           void *stream);
+
+/* Many instances at once: instance i has p[i] processors, root[i], and asks for
+ * the m physical ranks ranks[i*m .. i*m+m).  Row j of instance i, 2*q(p[i])
+ * int32 {recv[0..q-1], send[0..q-1]}, is written at
+ *     out[row_off[i] + j * 2*q(p[i])].
+ * p, root, ranks, row_off (n_inst+1 prefix sums, in int32 elements) and out are
+ * device arrays; out holds out_elems elements.  Nothing can be validated on
+ * the host without a copy, so the kernel does it: an instance with p outside
+ * the domain, root >= p, a row_off step other than m*2q, or rows beyond
+ * out_elems writes nothing, and a rank >= p[i] gets a row of INT32_MIN; each
+ * such instance or rank adds one to *n_rejected (device uint32, overwritten;
+ * may be NULL).  Errors: NULL pointers, m = 0 with n_inst > 0. */
+int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *root,
+                            const uint32_t *ranks, uint32_t m,
+                            const uint64_t *row_off, int32_t *out,
+                            uint64_t out_elems, uint32_t *n_rejected, void *stream);
+
+/* Bytes of device workspace bcast_simulate needs (0 on invalid arguments). */
+size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots);
+
+/* Algorithm 1 (and, for several roots side by side, Algorithm 7) replayed over
+ * possession bits: n blocks travel from each of the n_roots roots (host array
+ * `roots`) through n-1+q rounds.  In every round each non-root rank that
+ * expects a block checks that its from-processor sends that block and that
+ * it does not hold it yet, each rank that sends checks that it held the block
+ * before the round, and then the received block is marked.  Blocks < 0 are
+ * neither sent nor received, blocks > n-1 count as n-1, nothing is sent to
+ * the root.  After the last round every rank must hold all n blocks.
+ * sched: device int32 [n_roots][p][2q] (row r = recv then send of physical
+ * rank r for that root), or NULL to have the schedules computed here.
+ * workspace: device, at least bcast_simulate_workspace bytes, contents
+ * irrelevant on entry.  verdict: device, n_roots structs, overwritten.
+ * Errors: domain of p, n = 0, n_roots = 0, a root >= p, NULL pointers,
+ * workspace too small (BCAST_ENOMEM). */
+int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                   const int32_t *sched, void *workspace, size_t workspace_bytes,
+                   bcast_verdict *verdict, void *stream);
+
+/* Text for a return code; never NULL. */
+const char *bcast_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

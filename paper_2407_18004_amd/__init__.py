@@ -1,0 +1,13 @@
+"""MI355X (gfx950) library for round-optimal broadcast schedules.
+
+The product is the HIP shared library behind ``include/bcast.h``; this package
+is its thin Python binding (argument marshalling only) plus the seeded
+workload generators used by tests and the benchmark.  There is no CPU
+fallback: without the built library every call raises.
+"""
+from .binding import (  # noqa: F401
+    BCAST_OK, BCAST_EINVAL, BCAST_ENOMEM, BCAST_EHIP, BcastError, Verdict,
+    library_path, load_library, exported_symbols,
+    bcast_q, bcast_skips, bcast_schedules, bcast_schedules_digest,
+    bcast_schedules_batched, bcast_simulate_workspace, bcast_simulate, bcast_strerror,
+)

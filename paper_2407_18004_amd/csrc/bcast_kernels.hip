@@ -1,0 +1,554 @@
+// gfx950 kernels and the C ABI of include/bcast.h.
+//
+// Launch shape shared by the schedule kernels: workgroups of 256 lanes = four
+// wavefronts; a wavefront owns a tile of 64 consecutive ranks and never needs
+// a workgroup barrier.  Each lane computes one rank (Algorithms 3, 5, 6) with
+// its state in VGPRs and drops the 2q results as bytes into the wavefront's
+// slice of LDS, laid out exactly like the output rows, so that the tile leaves
+// the CU as 16-byte stores to consecutive addresses.  The grid is a fixed
+// number of workgroups that stride over the tiles.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/bcast.h"
+#include "bcast_device.hpp"
+
+using namespace bcast;
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kMaxFields = 62;                       // 2q for q = 31
+constexpr int kTileBytes = kWave * kMaxFields;       // 3968, a multiple of 16
+constexpr int kInvalidEntry = INT32_MIN;           // row of a rank that is not in its instance
+
+enum Layout : int { kInterleaved = 0, kSeparate = 1, kRowwise = 2 };
+
+// Orders the byte stores of the compute phase before the word loads of the
+// copy-out phase (and back) inside one wavefront.  LDS operations of a
+// wavefront complete in order, so no workgroup barrier is needed.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Copies n_bytes schedule bytes from LDS (4-byte aligned) to n_bytes int32 at
+// dst, all 64 lanes of the wavefront cooperating, widest stores possible.
+// With kMarkInvalid the byte kInvalidByte (never a schedule entry) widens to
+// kInvalidEntry instead of to itself.
+constexpr int kInvalidByte = -128;
+
+template <bool kMarkInvalid>
+__device__ __forceinline__ int widen(int byte_val) {
+  if (kMarkInvalid) return byte_val == kInvalidByte ? kInvalidEntry : byte_val;
+  return byte_val;
+}
+
+template <bool kMarkInvalid>
+__device__ __forceinline__ void tile_out(const uint32_t *lds_words, int32_t *dst,
+                                         uint32_t n_bytes, uint32_t lane) {
+  const uint32_t groups = n_bytes >> 2;
+  const int8_t *bytes = reinterpret_cast<const int8_t *>(lds_words);
+  if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+    int4 *dst4 = reinterpret_cast<int4 *>(dst);
+    for (uint32_t g = lane; g < groups; g += kWave) {
+      const uint32_t w = lds_words[g];
+      int4 o;
+      o.x = widen<kMarkInvalid>((int)(int8_t)(w & 0xFF));
+      o.y = widen<kMarkInvalid>((int)(int8_t)((w >> 8) & 0xFF));
+      o.z = widen<kMarkInvalid>((int)(int8_t)((w >> 16) & 0xFF));
+      o.w = widen<kMarkInvalid>((int)(int8_t)(w >> 24));
+      dst4[g] = o;
+    }
+  } else {
+    for (uint32_t i = lane; i < (groups << 2); i += kWave)
+      dst[i] = widen<kMarkInvalid>((int)bytes[i]);
+  }
+  for (uint32_t i = (groups << 2) + lane; i < n_bytes; i += kWave)
+    dst[i] = widen<kMarkInvalid>((int)bytes[i]);
+}
+
+// ---------------------------------------------------------------- schedules
+
+struct SchedParams {
+  uint32_t p, q, root;
+  uint64_t r_begin, n_ranks;
+  int32_t *recv, *send;
+  int64_t ld;
+  int layout;
+};
+
+__global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
+  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = threadIdx.x / kWave;
+  const Instance in = make_instance(prm.p, prm.q, prm.root);
+  const uint32_t q = prm.q;
+  int8_t *slice = reinterpret_cast<int8_t *>(lds[wave]);
+  // row pitch, and offset of the send part inside the slice
+  const uint32_t pitch = prm.layout == kSeparate ? q : 2u * q;
+  const uint32_t send_off = prm.layout == kSeparate ? kWave * q : q;
+  int8_t *recv_row = slice + lane * pitch;
+  int8_t *send_row = recv_row + send_off;
+
+  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
+  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+    const uint64_t row0 = tile * kWave;
+    const uint64_t left = prm.n_ranks - row0;
+    const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
+    if (lane < n_valid) {
+      const uint32_t r = (uint32_t)(prm.r_begin + row0 + lane);
+      int b;
+      compute_rank(in, virtual_rank(in, r), recv_row, send_row, b);
+    }
+    wave_lds_sync();
+    if (prm.layout == kInterleaved) {
+      tile_out<false>(lds[wave], prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
+    } else if (prm.layout == kSeparate) {
+      tile_out<false>(lds[wave], prm.recv + row0 * q, n_valid * q, lane);
+      tile_out<false>(lds[wave] + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
+    } else if (lane < n_valid) {
+      int32_t *rr = prm.recv + (row0 + lane) * (uint64_t)prm.ld;
+      int32_t *sr = prm.send + (row0 + lane) * (uint64_t)prm.ld;
+      for (uint32_t k = 0; k < q; ++k) { rr[k] = recv_row[k]; sr[k] = send_row[k]; }
+    }
+    wave_lds_sync();
+  }
+}
+
+// ------------------------------------------------------------------- digest
+
+struct DigestParams {
+  uint32_t p, q, root;
+  uint64_t r_begin, n_ranks;
+  uint64_t *digest;
+  uint32_t *flags;
+};
+
+__global__ void k_digest_init(uint64_t *digest, uint32_t *flags) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; }
+}
+
+__global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
+  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = threadIdx.x / kWave;
+  const Instance in = make_instance(prm.p, prm.q, prm.root);
+  const uint32_t q = prm.q;
+  int8_t *recv_row = reinterpret_cast<int8_t *>(lds[wave]) + lane * 2u * q;
+  int8_t *send_row = recv_row + q;
+
+  uint64_t acc = 0;
+  uint32_t acc_flags = 0;
+  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
+  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+    const uint64_t row = tile * kWave + lane;
+    if (row < prm.n_ranks) {
+      const uint32_t r = (uint32_t)(prm.r_begin + row);
+      const uint32_t v = virtual_rank(in, r);
+      int b;
+      uint32_t fl = compute_rank(in, v, recv_row, send_row, b);
+      uint64_t h;
+      uint32_t fl2;
+      digest_rank(in, r, v, b, recv_row, send_row, h, fl2);
+      acc ^= h;
+      acc_flags |= fl | fl2;
+    }
+  }
+  acc = wave_xor64(acc);
+  acc_flags = wave_or32(acc_flags);
+  if (lane == 0) {
+    atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
+    if (acc_flags) atomicOr(prm.flags, acc_flags);
+  }
+}
+
+// ------------------------------------------------------------------ batched
+
+struct BatchParams {
+  uint32_t n_inst, m, tiles_per_inst;
+  const uint32_t *p, *root, *ranks;
+  const uint64_t *row_off;
+  int32_t *out;
+  uint64_t out_elems;
+  uint32_t *n_rejected;
+};
+
+__global__ void k_u32_zero(uint32_t *x) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *x = 0;
+}
+
+__global__ __launch_bounds__(kBlock) void k_batched(BatchParams prm) {
+  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = threadIdx.x / kWave;
+  const uint64_t n_work = (uint64_t)prm.n_inst * prm.tiles_per_inst;
+  for (uint64_t work = (uint64_t)blockIdx.x * kWavesPerBlock + wave; work < n_work;
+       work += (uint64_t)gridDim.x * kWavesPerBlock) {
+    const uint32_t inst = (uint32_t)(work / prm.tiles_per_inst);
+    const uint32_t tile = (uint32_t)(work % prm.tiles_per_inst);
+    const uint32_t p = prm.p[inst];
+    const uint32_t root = prm.root[inst];
+    const uint32_t q = p > 1u ? 32u - (uint32_t)__clz((int)(p - 1u)) : 0u;
+    const uint64_t off0 = prm.row_off[inst], off1 = prm.row_off[inst + 1];
+    const bool inst_ok = p >= 1u && p <= BCAST_MAX_P && root < p && off1 >= off0 &&
+                         off1 - off0 == (uint64_t)prm.m * 2u * q && off1 <= prm.out_elems;
+    if (!inst_ok) {
+      if (tile == 0 && lane == 0 && prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
+      continue;
+    }
+    const Instance in = make_instance(p, q, root);
+    const uint32_t j0 = tile * kWave;
+    const uint32_t n_valid = prm.m - j0 < (uint32_t)kWave ? prm.m - j0 : (uint32_t)kWave;
+    int8_t *recv_row = reinterpret_cast<int8_t *>(lds[wave]) + lane * 2u * q;
+    int8_t *send_row = recv_row + q;
+    if (lane < n_valid) {
+      const uint32_t r = prm.ranks[(uint64_t)inst * prm.m + j0 + lane];
+      int b;
+      if (r < p) {
+        compute_rank(in, virtual_rank(in, r), recv_row, send_row, b);
+      } else {                           // rank outside the instance: marked row
+        for (uint32_t k = 0; k < 2u * q; ++k) recv_row[k] = (int8_t)kInvalidByte;
+        if (prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
+      }
+    }
+    wave_lds_sync();
+    tile_out<true>(lds[wave], prm.out + off0 + (uint64_t)j0 * 2u * q, n_valid * 2u * q, lane);
+    wave_lds_sync();
+  }
+}
+
+// ---------------------------------------------------------------- simulator
+
+constexpr int kSimBlock = 128;
+constexpr int kSimMaxQ = 31;
+
+struct SimParams {
+  uint32_t p, q, n, n_words, x;
+  uint32_t rounds;
+  const uint32_t *roots;         // device copy inside the workspace
+  const int32_t *sched;          // [n_roots][p][2q] physical, or NULL
+  const int32_t *table;          // [p][2q] by virtual rank (when sched == NULL)
+  uint32_t *possession;          // [n_roots][n_words][p]
+  bcast_verdict *verdict;
+};
+
+__global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rounds) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_roots) {
+    bcast_verdict z;
+    z.flags = 0; z.rounds = rounds;
+    z.n_bad_recv_dup = 0; z.n_bad_send_unheld = 0; z.n_edge_mismatch = 0;
+    z.n_incomplete_ranks = 0; z.first_bad = UINT64_MAX;
+    vd[i] = z;
+  }
+}
+
+// One lane per processor, one grid row per root.  A processor's possession
+// bits are written by its own lane only, and everything it needs from other
+// processors is schedule data, so the lane walks through all rounds by itself:
+// the sender-side check ("held before the round") reads the lane's own word
+// before this round's receive is marked.
+__global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
+  __shared__ int32_t st_recv[kSimMaxQ][kSimBlock];
+  __shared__ int32_t st_send[kSimMaxQ][kSimBlock];
+  __shared__ int32_t st_from[kSimMaxQ][kSimBlock];   // sendblock[k] of the from-processor
+  const uint32_t lane_b = threadIdx.x;
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t root_idx = blockIdx.y;
+  const uint32_t p = prm.p, q = prm.q, n = prm.n;
+  const uint32_t pm1 = p - 1u;
+  const uint32_t root = prm.roots[root_idx];
+  const uint32_t v = blockIdx.x * kSimBlock + lane_b;
+  const bool active = v < p;
+  const uint32_t r_phys = active ? (v + root >= p ? v + root - p : v + root) : 0u;
+
+  uint64_t n_dup = 0, n_unheld = 0, n_edge = 0, n_incomplete = 0, first_bad = UINT64_MAX;
+
+  if (active) {
+    const int32_t *own = prm.sched
+        ? prm.sched + ((uint64_t)root_idx * p + r_phys) * 2u * q
+        : prm.table + (uint64_t)v * 2u * q;
+    for (uint32_t k = 0; k < q; ++k) {
+      st_recv[k][lane_b] = own[k];
+      st_send[k][lane_b] = own[q + k];
+      const uint32_t sk = skip_at_level(pm1, q - k);
+      const uint32_t f = v >= sk ? v - sk : v + (p - sk);
+      const uint32_t f_phys = f + root >= p ? f + root - p : f + root;
+      const int32_t *frow = prm.sched
+          ? prm.sched + ((uint64_t)root_idx * p + f_phys) * 2u * q
+          : prm.table + (uint64_t)f * 2u * q;
+      st_from[k][lane_b] = frow[q + k];
+    }
+    uint32_t *col = prm.possession + (uint64_t)root_idx * prm.n_words * p + v;
+    for (uint32_t w = 0; w < prm.n_words; ++w) col[(uint64_t)w * p] = 0u;
+
+    if (v != 0) {
+      const int64_t nm1 = (int64_t)n - 1;
+      uint32_t k = prm.x % q;
+      int64_t shift = -(int64_t)prm.x + (int64_t)q * (prm.x / q);
+      for (uint32_t round = 0; round < prm.rounds; ++round) {
+        int64_t rb = (int64_t)st_recv[k][lane_b] + shift;
+        int64_t fb = (int64_t)st_from[k][lane_b] + shift;
+        int64_t sb = (int64_t)st_send[k][lane_b] + shift;
+        const bool has_r = rb >= 0, has_f = fb >= 0;
+        rb = rb > nm1 ? nm1 : rb;
+        fb = fb > nm1 ? nm1 : fb;
+        const uint64_t key = ((uint64_t)round << 32) | r_phys;
+        if (has_r != has_f || (has_r && rb != fb)) {
+          ++n_edge;
+          first_bad = key < first_bad ? key : first_bad;
+        }
+        const uint32_t sk = skip_at_level(pm1, q - k);
+        const bool to_root = v + sk == p;
+        if (sb >= 0 && !to_root) {                  // state before this round
+          sb = sb > nm1 ? nm1 : sb;
+          const uint32_t word = col[(uint64_t)((uint32_t)sb >> 5) * p];
+          if (((word >> ((uint32_t)sb & 31u)) & 1u) == 0) {
+            ++n_unheld;
+            first_bad = key < first_bad ? key : first_bad;
+          }
+        }
+        if (has_r) {
+          uint32_t *wp = col + (uint64_t)((uint32_t)rb >> 5) * p;
+          const uint32_t word = *wp;
+          const uint32_t bit = 1u << ((uint32_t)rb & 31u);
+          if (word & bit) {
+            ++n_dup;
+            first_bad = key < first_bad ? key : first_bad;
+          } else {
+            *wp = word | bit;
+          }
+        }
+        if (++k == q) { k = 0; shift += q; }
+      }
+      uint32_t have = 0;
+      for (uint32_t w = 0; w < prm.n_words; ++w) {
+        uint32_t word = col[(uint64_t)w * p];
+        if (w == prm.n_words - 1u && (n & 31u)) word &= (1u << (n & 31u)) - 1u;
+        have += (uint32_t)__popc(word);
+      }
+      if (have != n) {
+        n_incomplete = 1;
+        const uint64_t key = ((uint64_t)prm.rounds << 32) | r_phys;
+        first_bad = key < first_bad ? key : first_bad;
+      }
+    }
+  }
+
+  // wavefront reductions, then one atomic per counter that is not zero
+  const uint64_t bad_lanes = __ballot(n_incomplete != 0);
+  n_dup = wave_add64(n_dup);
+  n_unheld = wave_add64(n_unheld);
+  n_edge = wave_add64(n_edge);
+  first_bad = wave_min64(first_bad);
+  if (lane == 0) {
+    bcast_verdict *vd = prm.verdict + root_idx;
+    uint32_t fl = 0;
+    if (n_dup) { fl |= BCAST_V_RECV_DUP; atomicAdd((unsigned long long *)&vd->n_bad_recv_dup, (unsigned long long)n_dup); }
+    if (n_unheld) { fl |= BCAST_V_SEND_UNHELD; atomicAdd((unsigned long long *)&vd->n_bad_send_unheld, (unsigned long long)n_unheld); }
+    if (n_edge) { fl |= BCAST_V_EDGE; atomicAdd((unsigned long long *)&vd->n_edge_mismatch, (unsigned long long)n_edge); }
+    if (bad_lanes) { fl |= BCAST_V_INCOMPLETE; atomicAdd((unsigned long long *)&vd->n_incomplete_ranks, (unsigned long long)__popcll(bad_lanes)); }
+    if (fl) {
+      atomicOr(&vd->flags, fl);
+      atomicMin((unsigned long long *)&vd->first_bad, (unsigned long long)first_bad);
+    }
+  }
+}
+
+// --------------------------------------------------------------- host side
+
+int host_q(uint32_t p) {
+  if (p == 0 || p > BCAST_MAX_P) return BCAST_EINVAL;
+  int q = 0;
+  while ((1ull << q) < (uint64_t)p) ++q;
+  return q;
+}
+
+int persistent_grid(uint64_t n_blocks_wanted) {
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      return -1;
+    cus[dev] = n;
+  }
+  const uint64_t cap = (uint64_t)cus[dev] * 8u;
+  const uint64_t g = n_blocks_wanted < cap ? n_blocks_wanted : cap;
+  return (int)(g == 0 ? 1 : g);
+}
+
+bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+// ------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+int bcast_q(uint32_t p) { return host_q(p); }
+
+int bcast_skips(uint32_t p, uint32_t *skips, int *q_out) {
+  const int q = host_q(p);
+  if (q < 0 || !skips) return BCAST_EINVAL;
+  int k = q;
+  skips[k] = p;
+  while (k > 0) {                       // Algorithm 2
+    skips[k - 1] = skips[k] - skips[k] / 2u;
+    --k;
+  }
+  if (q_out) *q_out = q;
+  return BCAST_OK;
+}
+
+int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                    int32_t *recv, int32_t *send, int64_t ld, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || root >= p || r_begin > r_end || r_end > p) return BCAST_EINVAL;
+  const uint64_t n = r_end - r_begin;
+  if (n == 0 || q == 0) return BCAST_OK;
+  if (!recv || !send || ld < q) return BCAST_EINVAL;
+  SchedParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
+  prm.r_begin = r_begin; prm.n_ranks = n;
+  prm.recv = recv; prm.send = send; prm.ld = ld;
+  const int32_t *recv_end = recv + (n - 1) * (uint64_t)ld + q;
+  const int32_t *send_end = send + (n - 1) * (uint64_t)ld + q;
+  if (send == recv + q && ld == 2 * (int64_t)q) {
+    prm.layout = kInterleaved;
+  } else if (send >= recv_end || recv >= send_end) {
+    prm.layout = ld == q ? kSeparate : kRowwise;
+  } else {
+    // interleaved rows with padding: legal when every send row sits in the gap
+    // of the recv rows, i.e. the offset modulo ld leaves room for q entries
+    const int64_t d = send > recv ? send - recv : recv - send;
+    const int64_t m = d % ld;
+    if (m < q || ld - m < q) return BCAST_EINVAL;
+    prm.layout = kRowwise;
+  }
+  const uint64_t blocks = (n + kBlock - 1) / kBlock;
+  const int grid = persistent_grid(blocks);
+  if (grid < 0) return BCAST_EHIP;
+  hipLaunchKernelGGL(k_schedules, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                           uint64_t *digest, uint32_t *flags, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !digest || !flags)
+    return BCAST_EINVAL;
+  hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, (hipStream_t)stream, digest, flags);
+  if (!launch_ok()) return BCAST_EHIP;
+  const uint64_t n = r_end - r_begin;
+  if (n == 0) return BCAST_OK;
+  DigestParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
+  prm.r_begin = r_begin; prm.n_ranks = n;
+  prm.digest = digest; prm.flags = flags;
+  const int grid = persistent_grid((n + kBlock - 1) / kBlock);
+  if (grid < 0) return BCAST_EHIP;
+  hipLaunchKernelGGL(k_digest, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *root,
+                            const uint32_t *ranks, uint32_t m, const uint64_t *row_off,
+                            int32_t *out, uint64_t out_elems, uint32_t *n_rejected,
+                            void *stream) {
+  if (n_rejected) {
+    hipLaunchKernelGGL(k_u32_zero, dim3(1), dim3(64), 0, (hipStream_t)stream, n_rejected);
+    if (!launch_ok()) return BCAST_EHIP;
+  }
+  if (n_inst == 0) return BCAST_OK;
+  if (!p || !root || !ranks || !row_off || m == 0) return BCAST_EINVAL;
+  if (!out && out_elems != 0) return BCAST_EINVAL;
+  BatchParams prm;
+  prm.n_inst = n_inst; prm.m = m; prm.tiles_per_inst = (m + kWave - 1) / kWave;
+  prm.p = p; prm.root = root; prm.ranks = ranks; prm.row_off = row_off;
+  prm.out = out; prm.out_elems = out_elems; prm.n_rejected = n_rejected;
+  const uint64_t work = (uint64_t)n_inst * prm.tiles_per_inst;
+  const int grid = persistent_grid((work + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (grid < 0) return BCAST_EHIP;
+  hipLaunchKernelGGL(k_batched, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+// workspace: [roots: n_roots u32][table: p*2q int32][possession: n_roots*n_words*p u32]
+size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots) {
+  const int q = host_q(p);
+  if (q < 0 || n == 0 || n_roots == 0) return 0;
+  const size_t n_words = ((size_t)n + 31) / 32;
+  size_t bytes = align_up((size_t)n_roots * 4, 256);
+  bytes += align_up((size_t)p * 2 * (size_t)q * 4, 256);
+  bytes += align_up((size_t)n_roots * n_words * p * 4, 256);
+  return bytes + 256;
+}
+
+int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                   const int32_t *sched, void *workspace, size_t workspace_bytes,
+                   bcast_verdict *verdict, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || n == 0 || n > (1u << 30) || n_roots == 0 || n_roots > 65535u || !roots || !verdict)
+    return BCAST_EINVAL;
+  for (uint32_t i = 0; i < n_roots; ++i)
+    if (roots[i] >= p) return BCAST_EINVAL;
+  const size_t need = bcast_simulate_workspace(p, n, n_roots);
+  if (!workspace) return BCAST_EINVAL;
+  if (workspace_bytes < need) return BCAST_ENOMEM;
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t rounds = q == 0 ? 0u : n - 1u + (uint32_t)q;
+  hipLaunchKernelGGL(k_verdict_init, dim3((n_roots + 63) / 64), dim3(64), 0, st, verdict,
+                     n_roots, rounds);
+  if (!launch_ok()) return BCAST_EHIP;
+  if (q == 0) return BCAST_OK;          // p = 1: the root holds everything, no rounds
+
+  uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256);
+  uint32_t *d_roots = reinterpret_cast<uint32_t *>(base);
+  base += align_up((size_t)n_roots * 4, 256);
+  int32_t *table = reinterpret_cast<int32_t *>(base);
+  base += align_up((size_t)p * 2 * (size_t)q * 4, 256);
+  uint32_t *possession = reinterpret_cast<uint32_t *>(base);
+
+  // The roots array is small; it is copied through the stream so that the
+  // caller's host array may be reused as soon as the call returns.
+  if (hipMemcpyAsync(d_roots, roots, (size_t)n_roots * 4, hipMemcpyHostToDevice, st) != hipSuccess)
+    return BCAST_EHIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return BCAST_EHIP;
+
+  if (!sched) {
+    const int rc = bcast_schedules(p, 0, 0, p, table, table + q, 2 * (int64_t)q, stream);
+    if (rc != BCAST_OK) return rc;
+  }
+  SimParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.n = n; prm.n_words = (n + 31u) / 32u;
+  prm.x = ((uint32_t)q - (n - 1u) % (uint32_t)q) % (uint32_t)q;
+  prm.rounds = rounds;
+  prm.roots = d_roots; prm.sched = sched; prm.table = table;
+  prm.possession = possession; prm.verdict = verdict;
+  dim3 grid((p + kSimBlock - 1) / kSimBlock, n_roots);
+  hipLaunchKernelGGL(k_simulate, grid, dim3(kSimBlock), 0, st, prm);
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+const char *bcast_strerror(int code) {
+  switch (code) {
+    case BCAST_OK: return "ok";
+    case BCAST_EINVAL: return "argument outside the documented domain";
+    case BCAST_ENOMEM: return "workspace too small";
+    case BCAST_EHIP: return "HIP runtime error";
+    default: return "unknown bcast error code";
+  }
+}
+
+}  // extern "C"

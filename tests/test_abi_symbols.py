@@ -1,0 +1,52 @@
+"""The built HIP library loads and exports every function include/bcast.h
+declares.  Host-only entry points are also called; nothing here needs a GPU."""
+import ctypes
+import os
+
+import pytest
+
+import paper_2407_18004_amd as lib
+
+
+@pytest.fixture(scope="module")
+def built():
+    if not os.path.exists(lib.library_path()):
+        from paper_2407_18004_amd import build
+        build.build()
+    return lib.load_library()
+
+
+def test_every_declared_symbol_is_exported(built):
+    names = lib.exported_symbols()
+    assert set(names) >= {"bcast_q", "bcast_skips", "bcast_schedules", "bcast_schedules_digest",
+                          "bcast_schedules_batched", "bcast_simulate_workspace",
+                          "bcast_simulate", "bcast_strerror"}
+    for name in names:
+        assert isinstance(getattr(built, name), ctypes._CFuncPtr), name
+
+
+def test_host_only_entry_points(built):
+    assert lib.bcast_q(1) == 0 and lib.bcast_q(2) == 1 and lib.bcast_q(2**31 - 1) == 31
+    assert lib.bcast_skips(17) == [1, 2, 3, 5, 9, 17]          # Table 1
+    assert lib.bcast_skips(11) == [1, 2, 3, 6, 11]             # proof of Lemma 4
+    with pytest.raises(lib.BcastError):
+        lib.bcast_q(0)
+    with pytest.raises(lib.BcastError):
+        lib.bcast_q(2**31)
+    assert lib.bcast_strerror(0) == "ok"
+    assert lib.bcast_simulate_workspace(65537, 256, 64) >= 64 * 8 * 65537 * 4
+    assert lib.bcast_simulate_workspace(10, 0, 1) == 0
+
+
+def test_verdict_struct_layout():
+    from paper_2407_18004_amd.binding import Verdict
+    assert ctypes.sizeof(Verdict) == 48
+    assert Verdict.first_bad.offset == 40
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    from paper_2407_18004_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

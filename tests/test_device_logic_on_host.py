@@ -1,0 +1,93 @@
+"""The HIP library's per-rank device functions, compiled for the CPU with a
+small stand-in for the HIP header, against the oracle.  No GPU is involved:
+this checks the state-machine form of the receive search, the send walk, the
+32-bit arithmetic near p = 2^31 and the flag logic before anything is launched."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SHIM_DIR = os.path.join(HERE, "host_shim")
+SHIM_SO = os.path.join(SHIM_DIR, "libdevice_on_host.so")
+
+
+@pytest.fixture(scope="module")
+def shim():
+    src = os.path.join(SHIM_DIR, "device_on_host.cpp")
+    hdr = os.path.join(os.path.dirname(HERE), "paper_2407_18004_amd", "csrc", "bcast_device.hpp")
+    newest = max(os.path.getmtime(src), os.path.getmtime(hdr))
+    if not os.path.exists(SHIM_SO) or os.path.getmtime(SHIM_SO) < newest:
+        subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-I", SHIM_DIR,
+                        "-Wall", "-o", SHIM_SO, src], check=True)
+    lib = ctypes.CDLL(SHIM_SO)
+    lib.shim_schedules_ranks.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p]
+    lib.shim_digest_row.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                    ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.shim_digest_row.restype = None
+    return lib
+
+
+def shim_rows(lib, p, root, ranks):
+    ranks = np.ascontiguousarray(ranks, dtype=np.uint32)
+    q = oracle.q_of(p)
+    rows = np.zeros((ranks.size, 2 * q), dtype=np.int32)
+    flags = np.zeros(ranks.size, dtype=np.uint32)
+    hashes = np.zeros(ranks.size, dtype=np.uint64)
+    got_q = lib.shim_schedules_ranks(p, root, ranks.ctypes.data, ranks.size,
+                                     rows.ctypes.data if rows.size else None,
+                                     flags.ctypes.data, hashes.ctypes.data)
+    assert got_q == q
+    return rows, flags, hashes
+
+
+def test_all_ranks_small_p(shim):
+    for p in range(1, 2049):
+        rows, flags, hashes = shim_rows(shim, p, 0, np.arange(p))
+        want = oracle.schedules(p, send_mode=1)
+        assert np.array_equal(rows, want), p
+        assert not flags.any(), p
+        dg, fl = oracle.digest(p, 0, 0, p)
+        assert int(np.bitwise_xor.reduce(hashes)) == dg and fl == 0
+
+
+def test_roots_and_large_p(shim):
+    for p in (1000003, 65537, 2**31 - 1, 2**31 - 2, 2**30 + 1, 2**20, 3 * 2**28 + 5):
+        rng = np.random.default_rng(p + 1)
+        root = int(rng.integers(0, p))
+        ranks = np.unique(np.concatenate([
+            rng.integers(0, p, size=6000), np.arange(0, 70), np.arange(p - 70, p),
+            (root + np.arange(-3, 4)) % p])).astype(np.uint32)
+        rows, flags, hashes = shim_rows(shim, p, root, ranks)
+        want = oracle.schedules_ranks(p, root, ranks, send_mode=1)
+        assert np.array_equal(rows, want), p
+        assert not flags.any()
+        for j in range(0, len(ranks), 97):
+            h, fl = oracle.digest_row(p, root, int(ranks[j]), want[j, :want.shape[1] // 2],
+                                      want[j, want.shape[1] // 2:])
+            assert (h, fl) == (int(hashes[j]), 0)
+
+
+def test_flags_on_planted_mistakes(shim):
+    p, root = 1000, 17
+    q = oracle.q_of(p)
+    rng = np.random.default_rng(5)
+    for r in rng.integers(0, p, size=60):
+        r = int(r)
+        row = oracle.schedules_ranks(p, root, np.array([r]))[0]
+        for trial in range(12):
+            bad = row.copy()
+            pos = int(rng.integers(0, 2 * q))
+            bad[pos] = int(rng.integers(-q, q))
+            want = oracle.digest_row(p, root, r, bad[:q], bad[q:])
+            h = ctypes.c_uint64(0)
+            fl = ctypes.c_uint32(0)
+            bad = np.ascontiguousarray(bad, dtype=np.int32)
+            shim.shim_digest_row(p, root, r, bad.ctypes.data, ctypes.byref(h), ctypes.byref(fl))
+            assert (int(h.value), int(fl.value)) == want, (r, pos, bad.tolist())

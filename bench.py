@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the schedule hot path on one MI355X.
+
+One step = one pass of the whole path (skips, baseblock, receive search, send
+walk with violations, invariant flags and digest) over every rank of the huge
+streamed instance p = 2^31 - 1, root 0, in 32 chunks of 2^26 ranks, each chunk
+one call of bcast_schedules_digest.  Nothing crosses PCIe inside the timed
+region: the inputs are scalars and each chunk leaves 12 bytes in HBM.
+
+Prints ONE JSON line.  `roofline` prices the dominant kernel (k_digest, plain
+integer VALU work) against the chip's 32-bit lane-operation rate; the
+materialised table of p = 1,000,003 is timed as well and priced against HBM
+write bandwidth under `materialised`.  `cpu_baseline` is the CPU oracle timed
+on this machine's cores on a bounded sample of the same instance.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "rank-schedules/sec (recv+send, q=ceil(log2 p)) at p=2^31-1"
+UNIT = "rank-schedules/s"
+
+# MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit integer lane-operations.
+PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+PEAK_HBM = 8.0e12
+
+
+def lane_ops_per_rank(q: int) -> float:
+    """Algorithmic 32-bit lane-operations of one rank-schedule in digest mode.
+
+    Counted from the straight-line per-rank algorithm as this library states it
+    (one operation = one 32-bit integer instruction of one lane; a 64-bit
+    multiply of the hash counts as its four 32-bit multiplies plus adds):
+      baseblock walk      6 per level, q levels
+      receive search      24 per step of the state machine, 2.2 q steps on average
+                          (scans of Algorithm 4 measured with the oracle's counters)
+      send walk           16 per round, q rounds
+      flags + packing     17 per entry, 2q entries
+      hash                44 per SplitMix64 call, 1 + ceil(2q / 10) calls
+    Violations (rare at p = 2^31 - 1) are not counted.
+    """
+    calls = 1 + (2 * q + 9) // 10
+    return 6.0 * q + 24.0 * 2.2 * q + 16.0 * q + 17.0 * 2 * q + 44.0 * calls
+
+
+def run(args) -> dict:
+    import torch
+
+    import paper_2407_18004_amd as lib
+    from paper_2407_18004_amd import workloads
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    lib.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    p = workloads.STREAMED_P
+    q = lib.bcast_q(p)
+    chunks = workloads.streamed_chunks()
+    n_chunks = len(chunks)
+    dg = torch.zeros(n_chunks, dtype=torch.int64, device=dev)
+    fl = torch.zeros(n_chunks, dtype=torch.int32, device=dev)
+    dgs = [dg[i:i + 1] for i in range(n_chunks)]
+    fls = [fl[i:i + 1] for i in range(n_chunks)]
+
+    def step(events=None):
+        for i, (a, b) in enumerate(chunks):
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            lib.bcast_schedules_digest(p, 0, a, b, dgs[i], fls[i])
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = p / (ms_per_step * 1e-3)
+    flags_or = int(torch.bitwise_or(fl[0], fl.max()).item()) if n_chunks else 0
+    assert int(fl.abs().sum().item()) == 0, "invariant flags raised on the GPU"
+    whole = 0
+    for x in dg.cpu().tolist():
+        whole ^= x & ((1 << 64) - 1)
+
+    launch_ms = [a.elapsed_time(b) for a, b in events]
+    avg_launch_ms = sum(launch_ms) / len(launch_ms)
+    ranks_per_launch = p / n_chunks
+    achieved = lane_ops_per_rank(q) * ranks_per_launch / (avg_launch_ms * 1e-3)
+    roofline = {
+        "kernel": "k_digest", "bound": "alu",
+        "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+        "frac": achieved / PEAK_LANE_OPS,
+        "traffic": load_traffic("k_digest"),
+        "avg_launch_ms": avg_launch_ms, "launches": len(launch_ms),
+        "lane_ops_per_rank": lane_ops_per_rank(q),
+    }
+
+    out = {
+        "metric": METRIC, "value": value, "unit": UNIT, "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": "streamed instance p=2^31-1, root=0, all ranks in 32 chunks of "
+                               "2^26, digest+flags per chunk (bcast_schedules_digest)",
+                   "p": p, "q": q, "chunks": n_chunks, "digest": f"{whole:016x}",
+                   "flags": flags_or},
+        "roofline": roofline,
+        "materialised": bench_materialised(torch, lib, workloads, dev, args),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(p, whole_digest=None)
+    return out
+
+
+def bench_materialised(torch, lib, workloads, dev, args) -> dict:
+    """The [p][2q] table of p = 1,000,003 (q = 20): 8q bytes written per rank."""
+    p = workloads.MATERIALISED_P
+    q = lib.bcast_q(p)
+    table = torch.empty((p, 2 * q), dtype=torch.int32, device=dev)
+    reps = max(20, 4 * args.steps)
+    for _ in range(3):
+        lib.bcast_schedules(p, 0, 0, p, table, table, 2 * q, send_offset=q)
+    torch.cuda.synchronize()
+    evs = []
+    for _ in range(reps):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        lib.bcast_schedules(p, 0, 0, p, table, table, 2 * q, send_offset=q)
+        e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    med = ms[len(ms) // 2]
+    nbytes = 8.0 * q * p
+    return {
+        "workload": "p=1000003 root=0 all ranks, int32 [p][40] table (bcast_schedules)",
+        "kernel": "k_schedules", "median_launch_ms": med, "launches": reps,
+        "rank_schedules_per_s": p / (med * 1e-3),
+        "roofline": {"bound": "hbm", "achieved": nbytes / (med * 1e-3) / 1e9,
+                     "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                     "frac": nbytes / (med * 1e-3) / PEAK_HBM,
+                     "traffic": load_traffic("k_schedules")},
+    }
+
+
+def load_traffic(kernel: str):
+    """HBM bytes per launch from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(p: int, whole_digest=None) -> dict:
+    """The oracle (Algorithms 5 and 6 in plain C, OpenMP over ranks) on this
+    machine's cores, on a prefix of the same instance sized for 10-30 s."""
+    import oracle
+    threads = oracle.default_threads()
+    probe = 1 << 22
+    t0 = time.perf_counter()
+    oracle.digest(p, 0, 0, probe, send_mode=1, threads=threads)
+    rate = probe / (time.perf_counter() - t0)
+    n = int(min(p, max(probe, rate * 12.0)))
+    t0 = time.perf_counter()
+    oracle.digest(p, 0, 0, n, send_mode=1, threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": UNIT, "cores": threads, "kind": "oracle",
+            "sample": f"ranks [0, {n}) of p=2^31-1, digest+flags, {dt:.1f} s"}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (rank-schedules are independent; "
+                         "nothing is exchanged between GPUs). Run it with --gpus 1.")
+    print(json.dumps(run(args)), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -52,7 +52,7 @@ extern "C" {
 #define BCAST_F_COND4      (1u << 2) /* a send[k] is neither b-q nor an earlier recv[j] */
 #define BCAST_F_VIOLATIONS (1u << 3) /* more than four violations in Algorithm 6        */
 #define BCAST_F_SEARCH     (1u << 4) /* the receive search ended early or left its
-                                        expected shape (see DESIGN notes in the source) */
+                                        expected shape (explained at recv_search in the source) */
 #define BCAST_F_RANGE      (1u << 5) /* an entry outside [-q, q-1]                      */
 
 /* Flags of bcast_verdict.flags. */

@@ -36,10 +36,11 @@ __device__ __forceinline__ uint32_t next_level(uint32_t live, uint32_t j) {
 __device__ __forceinline__ uint32_t baseblock_level(uint32_t pm1, uint32_t q, uint32_t v) {
   uint32_t rem = v, jb = 0;
   for (uint32_t j = 1; j <= q; ++j) {
-    const uint32_t sk = skip_at_level(pm1, j);
-    const bool take = sk <= rem;
-    rem = take ? rem - sk : rem;
-    jb = take ? j : jb;
+    const uint32_t sk = skip_at_level(pm1, j);   // same for all lanes: a scalar
+    const uint32_t t = rem - sk;                 // wraps above rem when sk > rem
+    const uint32_t nr = t < rem ? t : rem;
+    jb = nr != rem ? j : jb;
+    rem = nr;
   }
   return jb;
 }
@@ -127,7 +128,8 @@ __device__ __forceinline__ uint32_t recv_search(uint32_t p, uint32_t pm1, uint32
 
 // Algorithm 6 without its violations: writes sendblock[k] through emit for
 // k = q-1 .. 0 and returns the mask of rounds k whose entry must instead be
-// taken from the receive schedule of the to-processor.
+// taken from the receive schedule of the to-processor.  All lanes are in the
+// same round k, so skip[k] and skip[k-1] are scalars.
 template <typename Emit>
 __device__ __forceinline__ uint32_t send_walk(uint32_t p, uint32_t pm1, uint32_t q,
                                               uint32_t v, int b, Emit emit) {
@@ -135,22 +137,29 @@ __device__ __forceinline__ uint32_t send_walk(uint32_t p, uint32_t pm1, uint32_t
   uint32_t viol = 0;
   uint32_t rp = v, e = p;
   int c = b;
-  const bool is_root = v == 0;
   for (uint32_t k = q - 1; k >= 1; --k) {
     const uint32_t skk = skip_at_level(pm1, q - k);
     const uint32_t skm = skip_at_level(pm1, q - k + 1);
+    const bool k_is_1 = k == 1;
     const bool lower = rp < skk;
-    const bool ok_lower = (rp + skk < e) || (e < skm) || (k == 1 && b > 0);
-    const bool ok_upper = (k == 1) || (rp > skk) || (e - skk < skm) || (rp + skk <= e);
+    const uint32_t s1 = rp + skk;
+    const uint32_t em = e - skk;               // meaningful in the upper part only
+    const bool ok_lower = (s1 < e) || (e < skm) || (k_is_1 && b > 0);
+    const bool ok_upper = k_is_1 || (rp > skk) || (em < skm) || (s1 <= e);
+    const bool bad = lower ? !ok_lower : !ok_upper;
+    viol = (viol << 1) | (uint32_t)bad;         // round k ends up at bit k - 1
     c = lower ? c : (int)k - (int)q;
-    const bool ok = lower ? ok_lower : ok_upper;
-    viol |= (ok || is_root) ? 0u : (1u << k);
-    const uint32_t e_lo = e > skk ? skk : e;
-    e = lower ? e_lo : e - skk;
-    rp = lower ? rp : rp - skk;
-    emit(k, is_root ? (int)k : c);
+    e = lower ? (e < skk ? e : skk) : em;
+    const uint32_t rm = rp - skk;               // wraps above rp in the lower part
+    rp = rm < rp ? rm : rp;
+    emit(k, c);
   }
-  emit(0u, is_root ? 0 : b - (int)q);
+  emit(0u, b - (int)q);
+  viol <<= 1;
+  if (v == 0) {                                 // the root sends block k in round k
+    for (uint32_t k = 0; k < q; ++k) emit(k, (int)k);
+    viol = 0;
+  }
   return viol;
 }
 
@@ -177,28 +186,145 @@ __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r)
   return r >= in.root ? r - in.root : r + (in.p - in.root);
 }
 
-// Computes the 2q entries of virtual rank v into LDS: recvblock[k] at
-// recv_row[k], sendblock[k] at send_row[k] (bytes).  Returns the search flags
-// (BCAST_F_SEARCH, BCAST_F_VIOLATIONS) and the baseblock through b_out.
-__device__ __forceinline__ uint32_t compute_rank(const Instance &in, uint32_t v,
-                                                 int8_t *recv_row, int8_t *send_row,
-                                                 int &b_out) {
+// The receive search again, in the form the kernels use: same state and same
+// tests as recv_search, reorganised around how the search actually runs.
+//
+// 1. Descent.  With k = 0 the search first walks down the list once: a skip
+//    that still leaves room for skip[1] = 2 is pushed (recursive call), the one
+//    that lands exactly on R - 1 is accepted for round 0, everything else is
+//    passed over.  With W = D - 2 this is "push if skip <= W, accept if
+//    skip = W + 1".  All lanes look at the same level in the same iteration,
+//    so the skip is a scalar and the body is a handful of instructions.
+// 2. Ascent.  What follows is an irregular mix of returns, accepts and short
+//    new descents; it runs as one branch-free step per iteration in which
+//    every lane makes whichever move its state asks for.
+//
+// The first call is for index q (skip p): for v >= 2 it is always a recursive
+// call, so the walk starts below it with D = v and level 0 on the path; for
+// the root level 0 is not in the list and the walk starts with D = p.  v = 1
+// (level 0 accepted directly, D = p + 1) is left to recv_search by the caller.
+template <typename Emit>
+__device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, uint32_t q,
+                                                     uint32_t v, uint32_t jb, uint32_t k_last,
+                                                     bool &anomaly, Emit emit) {
+  const bool is_root = v == 0;
+  const int b = (int)q - (int)jb;
+  // Descent.  W = D - 2 as a signed number; after the accept W = -1, which
+  // neither fits nor hits any more.  `pathr` holds the pending calls with level
+  // j at bit 31 - j, so that the deepest one is the lowest set bit.
+  int W = (int)((is_root ? p : v) - 2u);
+  uint32_t pathr = is_root ? 0u : 0x80000000u;
+  uint32_t jd = 0;
+  uint32_t anom = 0;
+  for (uint32_t j = 1; j <= q; ++j) {
+    const int sk = (int)skip_at_level(pm1, j);           // uniform: scalar
+    const int t = W - sk;
+    const bool take = j != jb && t >= -1;                 // push (t >= 0) or accept (t = -1)
+    const bool push = take && t >= 0;
+    // the call made for this index would look at the index again
+    // (skip + 1 <= D - skip): that look never passes
+    anom |= (uint32_t)(push && sk <= t + 1);
+    jd = (take && !push) ? j : jd;
+    W = take ? t : W;
+    pathr |= push ? (0x80000000u >> j) : 0u;
+  }
+  const bool hit = W == -1;
+  uint32_t live = (q >= 31 ? 0xFFFFFFFFu : ((2u << q) - 1u)) & ~(1u << jb);
+  uint32_t D = hit ? (uint32_t)skip_at_level(pm1, jd) + 1u : (uint32_t)(W + 2);
+  uint32_t k = 0, j = kEndLevel;
+  uint32_t M = 1u;                                        // max(skip[k], Sd + 1)
+  uint32_t sk1 = 2u;                                      // skip[k + 1]
+  if (hit) {                                              // round 0 accepted at level jd
+    emit(0u, -(int)jd);
+    live &= ~(1u << jd);
+    k = 1;
+    M = 2u;                                               // skip[1] = 2, Sd = 1
+    sk1 = q >= 2 ? skip_at_level(pm1, q - 2) : 0xFFFFFFFFu;
+    j = next_level(live, jd);
+  }
+  // Ascent.
+  const uint32_t k_stop = k_last + 1u < q ? k_last + 1u : q;
+  const uint32_t cap = 8u * q + 16u;
+  bool go = k < k_stop && !((int)j < 0 && pathr == 0);
+  for (uint32_t it = 0; it < cap && go; ++it) {
+    const bool is_end = (int)j < 0;
+    const uint32_t jp = 31u - (uint32_t)(__ffs((int)pathr) - 1);
+    const uint32_t jj = is_end ? jp : j;
+    const uint32_t a = skip_at_level(pm1, jj);
+    const uint32_t D1 = D + (is_end ? a : 0u);
+    const uint32_t t = D1 - a;
+    const bool pass = !is_end && a <= D1 && t >= M;
+    const bool rec = pass && t >= sk1;
+    const bool post = is_end || (pass && !rec);
+    const bool acc = post && D1 >= sk1;
+    const bool ret = post && D1 < sk1;
+    anom |= (uint32_t)(rec && a <= t && t - a >= M);
+    D = rec ? t : D1;
+    pathr ^= (is_end || rec) ? (0x80000000u >> jj) : 0u;
+    if (acc) {
+      emit(k, jj == 0 ? b : -(int)jj);
+      live ^= 1u << jj;
+      M = sk1 > t + 1u ? sk1 : t + 1u;
+      ++k;
+      sk1 = skip_at_level(pm1, (q - k - 1u) & 31u);       // skip[k+1]; unused once k = q
+    }
+    j = ret ? kEndLevel : next_level(live, jj);
+    go = k < k_stop && !((int)j < 0 && pathr == 0);
+  }
+  anomaly = anomaly || anom != 0 || (k < k_stop);
+  return k;
+}
+
+// Phase one of a rank: baseblock, receive schedule, send walk.  Writes
+// recvblock[k] to recv_row[k] and sendblock[k] to send_row[k] (bytes), returns
+// the mask of violation rounds still to be filled in, the baseblock and flags.
+__device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
+                                                        int8_t *recv_row, int8_t *send_row,
+                                                        int &b_out, uint32_t &flags) {
   const uint32_t q = in.q;
-  uint32_t flags = 0;
+  flags = 0;
   const uint32_t jb = baseblock_level(in.pm1, q, v);
   const int b = (int)q - (int)jb;
   b_out = b;
   if (q == 0) return 0;
   bool anomaly = false;
-  const uint32_t produced =
-      recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly,
-                  [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; });
+  uint32_t produced;
+  auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
+  if (v == 1u) produced = recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
+  else produced = recv_search_fast(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
-
-  uint32_t viol = send_walk(in.p, in.pm1, q, v, b,
-                            [&](uint32_t k, int val) { send_row[k] = (int8_t)val; });
+  const uint32_t viol = send_walk(in.p, in.pm1, q, v, b,
+                                  [&](uint32_t k, int val) { send_row[k] = (int8_t)val; });
   if (__popc(viol) > 4) flags |= BCAST_F_VIOLATIONS;
-  // Violations of Algorithm 6: entry k is recvblock[k] of the to-processor.
+  return viol;
+}
+
+// Phase two, for tiles of consecutive ranks: a violation in round k needs
+// recvblock[k] of rank r + skip[k]; if that rank sits `skip[k]` lanes further
+// in the same tile its row is already in LDS (row_pitch bytes per lane).
+// Returns the violations that are still open.  Call after the tile's phase one
+// is complete and visible.
+__device__ __forceinline__ uint32_t resolve_from_tile(const Instance &in, uint32_t viol,
+                                                      const int8_t *recv_row, int8_t *send_row,
+                                                      uint32_t row_pitch, uint32_t lane,
+                                                      uint32_t n_valid) {
+  uint32_t open = 0;
+  while (viol != 0) {
+    const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
+    viol &= viol - 1u;
+    const uint32_t sk = skip_at_level(in.pm1, in.q - k);
+    if (sk < n_valid && lane < n_valid - sk) send_row[k] = recv_row[sk * row_pitch + k];
+    else open |= 1u << k;
+  }
+  return open;
+}
+
+// Phase three: the remaining violations of Algorithm 6, each by a receive
+// search for the to-processor that stops once entry k is out.
+__device__ __forceinline__ uint32_t resolve_by_search(const Instance &in, uint32_t v,
+                                                      uint32_t viol, int8_t *send_row) {
+  const uint32_t q = in.q;
+  uint32_t flags = 0;
   while (viol != 0) {
     const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
     viol &= viol - 1u;
@@ -207,74 +333,67 @@ __device__ __forceinline__ uint32_t compute_rank(const Instance &in, uint32_t v,
     const uint32_t jbt = baseblock_level(in.pm1, q, t);
     int val = 0;
     bool anomaly_t = false;
-    const uint32_t got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t,
-                                     [&](uint32_t kk, int x) { if (kk == k) val = x; });
+    auto take = [&](uint32_t kk, int x) { if (kk == k) val = x; };
+    uint32_t got;
+    if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
+    else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
     if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
     send_row[k] = (int8_t)val;
   }
   return flags;
 }
 
+// All phases for a rank on its own (no neighbours to borrow from).
+__device__ __forceinline__ uint32_t compute_rank(const Instance &in, uint32_t v,
+                                                 int8_t *recv_row, int8_t *send_row,
+                                                 int &b_out) {
+  uint32_t flags;
+  const uint32_t viol = compute_rank_phase1(in, v, recv_row, send_row, b_out, flags);
+  return flags | resolve_by_search(in, v, viol, send_row);
+}
+
 // Invariant flags (Conditions 3 and 4, first send, range) and the row hash of
-// one rank from its 2q bytes in LDS.
+// one rank from its 2q bytes: row[0..q-1] = recvblock, row[q..2q-1] = sendblock.
+//
+// Flags: values v in [-q, q-1] are bit v + q of a 64-bit set.  `seen` collects
+// recvblock[0..k-1]; Condition 3 holds iff after q entries it is exactly the
+// expected set, Condition 4 iff every sendblock[k], k >= 1, is in seen + {b - q}.
+// Hash: ten six-bit fields per word, in field order.
 __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint32_t v, int b,
-                                            const int8_t *recv_row, const int8_t *send_row,
-                                            uint64_t &hash, uint32_t &flags) {
-  const int q = (int)in.q;
-  const uint32_t two_q = 2u * in.q;
+                                            const int8_t *row, uint64_t &hash, uint32_t &flags) {
+  const uint32_t q = in.q;
+  const uint32_t two_q = 2u * q;
   const bool is_root = v == 0;
-  uint32_t seen = 0, dup = 0, npos = 0, have_neg = 0, have_pos = 0;
-  bool range_bad = false, pos_ok = true, send0_ok = true, cond4_ok = true;
-  if (!is_root) have_neg = 1u << b;                 // b - q may always be sent
+  uint64_t seen = 0;
+  uint32_t bad_range = 0, bad_c4 = 0, bad_s0 = 0;
+  const uint64_t always = is_root ? 0ull : 1ull << b;          // b - q may always be sent
+  for (uint32_t k = 0; k < q; ++k) {
+    const uint32_t ur = (uint32_t)((int)row[k] + (int)q);
+    const uint32_t us = (uint32_t)((int)row[q + k] + (int)q);
+    bad_range |= (uint32_t)(ur >= two_q) | (uint32_t)(us >= two_q);
+    const uint64_t allowed = seen | always;
+    bad_c4 |= (uint32_t)(((allowed >> (us & 63u)) & 1ull) == 0ull && k != 0);
+    bad_s0 |= (uint32_t)(is_root ? us != q + k : (k == 0 && us != (uint32_t)b));
+    seen |= 1ull << (ur & 63u);
+  }
+  const uint64_t low = q >= 32 ? 0xFFFFFFFFull : ((1ull << q) - 1ull);
+  const uint64_t want = is_root ? low : ((low ^ (1ull << b)) | (1ull << (q + (uint32_t)b)));
+  flags = (seen == want && bad_range == 0 ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
+          ((bad_c4 && !is_root) ? BCAST_F_COND4 : 0u) | (bad_range ? BCAST_F_RANGE : 0u);
+
   uint64_t h = sm64(((uint64_t)in.p << 32) ^ (uint64_t)r);
-  uint64_t w = 0;
-  uint32_t sh = 0;
-  for (int k = 0; k < q; ++k) {
-    const int rv = recv_row[k];
-    w |= (uint64_t)((uint32_t)(rv + 32) & 63u) << sh;
-    sh += 6;
-    if (sh == 60) { h = sm64(h ^ w); w = 0; sh = 0; }
-    const bool in_range = (uint32_t)(rv + q) < two_q;
-    range_bad |= !in_range;
-    if (in_range) {
-      const uint32_t bit = 1u << (rv < 0 ? rv + q : rv);
-      dup |= seen & bit;
-      seen |= bit;
-      npos += rv >= 0 ? 1u : 0u;
-      pos_ok = pos_ok && (rv < 0 || rv == b);
+  for (uint32_t f0 = 0; f0 < two_q; f0 += 10) {
+    uint32_t lo = 0, hi = 0;                                     // fields 0-4 and 5-9 of the word
+#pragma unroll
+    for (uint32_t t = 0; t < 5; ++t) {
+      const uint32_t fa = f0 + t < two_q ? ((uint32_t)(int)row[f0 + t] + 32u) & 63u : 0u;
+      const uint32_t fb = f0 + 5 + t < two_q ? ((uint32_t)(int)row[f0 + 5 + t] + 32u) & 63u : 0u;
+      lo |= fa << (6u * t);
+      hi |= fb << (6u * t);
     }
+    h = sm64(h ^ ((uint64_t)lo | ((uint64_t)hi << 30)));
   }
-  for (int k = 0; k < q; ++k) {
-    const int sv = send_row[k];
-    const int rv = recv_row[k];
-    w |= (uint64_t)((uint32_t)(sv + 32) & 63u) << sh;
-    sh += 6;
-    if (sh == 60) { h = sm64(h ^ w); w = 0; sh = 0; }
-    const bool s_in = (uint32_t)(sv + q) < two_q;
-    range_bad |= !s_in;
-    if (is_root) {
-      send0_ok = send0_ok && sv == k;
-    } else {
-      if (k == 0) {
-        send0_ok = sv == b - q;
-      } else {
-        bool ok = false;
-        if (s_in) ok = sv < 0 ? ((have_neg >> (sv + q)) & 1u) != 0 : ((have_pos >> sv) & 1u) != 0;
-        cond4_ok = cond4_ok && ok;
-      }
-      if ((uint32_t)(rv + q) < two_q) {
-        if (rv < 0) have_neg |= 1u << (rv + q); else have_pos |= 1u << rv;
-      }
-    }
-  }
-  if (sh != 0) h = sm64(h ^ w);
-  const uint32_t full = q >= 32 ? 0xFFFFFFFFu : ((1u << q) - 1u);
-  // q in-range entries that set q different bits, one of them (none for the
-  // root) non-negative and equal to b: the multiset of Condition 3.
-  const bool cond3_ok = dup == 0 && seen == full && npos == (is_root ? 0u : 1u) && pos_ok;
   hash = h;
-  flags = (cond3_ok ? 0u : BCAST_F_COND3) | (send0_ok ? 0u : BCAST_F_SEND0) |
-          (cond4_ok ? 0u : BCAST_F_COND4) | (range_bad ? BCAST_F_RANGE : 0u);
 }
 
 __device__ __forceinline__ uint64_t wave_xor64(uint64_t x) {

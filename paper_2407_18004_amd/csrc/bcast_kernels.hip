@@ -101,10 +101,18 @@ __global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
     const uint64_t row0 = tile * kWave;
     const uint64_t left = prm.n_ranks - row0;
     const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
+    uint32_t v = 0, viol = 0;
     if (lane < n_valid) {
       const uint32_t r = (uint32_t)(prm.r_begin + row0 + lane);
       int b;
-      compute_rank(in, virtual_rank(in, r), recv_row, send_row, b);
+      uint32_t fl;
+      v = virtual_rank(in, r);
+      viol = compute_rank_phase1(in, v, recv_row, send_row, b, fl);
+    }
+    wave_lds_sync();
+    if (lane < n_valid) {
+      viol = resolve_from_tile(in, viol, recv_row, send_row, pitch, lane, n_valid);
+      resolve_by_search(in, v, viol, send_row);
     }
     wave_lds_sync();
     if (prm.layout == kInterleaved) {
@@ -149,17 +157,27 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
   for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
        tile += (uint64_t)gridDim.x * kWavesPerBlock) {
     const uint64_t row = tile * kWave + lane;
-    if (row < prm.n_ranks) {
-      const uint32_t r = (uint32_t)(prm.r_begin + row);
-      const uint32_t v = virtual_rank(in, r);
-      int b;
-      uint32_t fl = compute_rank(in, v, recv_row, send_row, b);
+    const uint64_t left = prm.n_ranks - tile * kWave;
+    const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
+    const bool valid = lane < n_valid;
+    const uint32_t r = (uint32_t)(prm.r_begin + row);
+    uint32_t v = 0, viol = 0, fl = 0;
+    int b = 0;
+    if (valid) {
+      v = virtual_rank(in, r);
+      viol = compute_rank_phase1(in, v, recv_row, send_row, b, fl);
+    }
+    wave_lds_sync();
+    if (valid) {
+      viol = resolve_from_tile(in, viol, recv_row, send_row, 2u * q, lane, n_valid);
+      fl |= resolve_by_search(in, v, viol, send_row);
       uint64_t h;
       uint32_t fl2;
-      digest_rank(in, r, v, b, recv_row, send_row, h, fl2);
+      digest_rank(in, r, v, b, recv_row, h, fl2);
       acc ^= h;
       acc_flags |= fl | fl2;
     }
+    wave_lds_sync();
   }
   acc = wave_xor64(acc);
   acc_flags = wave_or32(acc_flags);

@@ -32,10 +32,52 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
     for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = buf[k];
     uint64_t h = 0;
     uint32_t fl2 = 0;
-    digest_rank(in, ranks[i], v, b, buf, buf + q, h, fl2);
+    digest_rank(in, ranks[i], v, b, buf, h, fl2);
     if (flags_out) flags_out[i] = fl | fl2;
     if (hash_out) hash_out[i] = h;
   }
+  return (int)q;
+}
+
+// The same for n consecutive physical ranks from r_begin, in tiles of 64 lanes
+// the way a wavefront works through them: phase one for every lane, then
+// violations filled in from rows of the same tile, then the rest by search.
+int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n,
+                         int32_t *rows, uint32_t *flags_out, uint64_t *hash_out,
+                         uint64_t *n_from_tile) {
+  const uint32_t q = q_of(p);
+  const Instance in = make_instance(p, q, root);
+  uint64_t borrowed = 0;
+  for (uint64_t row0 = 0; row0 < n; row0 += 64) {
+    const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
+    int8_t tile[64 * 62];
+    memset(tile, 0x55, sizeof tile);
+    uint32_t viol[64], fl[64], vr[64];
+    int b[64];
+    for (uint32_t lane = 0; lane < n_valid; ++lane) {
+      vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
+      viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
+                                       tile + lane * 2 * q + q, b[lane], fl[lane]);
+    }
+    for (uint32_t lane = 0; lane < n_valid; ++lane) {
+      int8_t *recv_row = tile + lane * 2 * q;
+      const uint32_t open = resolve_from_tile(in, viol[lane], recv_row, recv_row + q, 2 * q,
+                                              lane, n_valid);
+      borrowed += (uint64_t)__popc(viol[lane] ^ open);
+      fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
+    }
+    for (uint32_t lane = 0; lane < n_valid; ++lane) {
+      const uint64_t i = row0 + lane;
+      const int8_t *recv_row = tile + lane * 2 * q;
+      for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = recv_row[k];
+      uint64_t h = 0;
+      uint32_t fl2 = 0;
+      digest_rank(in, (uint32_t)(r_begin + i), vr[lane], b[lane], recv_row, h, fl2);
+      if (flags_out) flags_out[i] = fl[lane] | fl2;
+      if (hash_out) hash_out[i] = h;
+    }
+  }
+  if (n_from_tile) *n_from_tile = borrowed;
   return (int)q;
 }
 
@@ -48,7 +90,7 @@ void shim_digest_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row,
   for (uint32_t k = 0; k < 2 * q; ++k) buf[k] = (int8_t)row[k];
   const uint32_t v = virtual_rank(in, r);
   const int b = (int)q - (int)baseblock_level(in.pm1, q, v);
-  digest_rank(in, r, v, b, buf, buf + q, *hash, *flags);
+  digest_rank(in, r, v, b, buf, *hash, *flags);
 }
 
 }  // extern "C"

@@ -31,6 +31,9 @@ def shim():
     lib.shim_digest_row.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_digest_row.restype = None
+    lib.shim_schedules_tiles.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p]
     return lib
 
 
@@ -45,6 +48,34 @@ def shim_rows(lib, p, root, ranks):
                                      flags.ctypes.data, hashes.ctypes.data)
     assert got_q == q
     return rows, flags, hashes
+
+
+def shim_tiles(lib, p, root, r_begin, n):
+    q = oracle.q_of(p)
+    rows = np.zeros((n, 2 * q), dtype=np.int32)
+    flags = np.zeros(n, dtype=np.uint32)
+    hashes = np.zeros(n, dtype=np.uint64)
+    borrowed = ctypes.c_uint64(0)
+    lib.shim_schedules_tiles(p, root, r_begin, n, rows.ctypes.data if rows.size else None,
+                             flags.ctypes.data, hashes.ctypes.data, ctypes.byref(borrowed))
+    return rows, flags, hashes, int(borrowed.value)
+
+
+def test_tiles_of_consecutive_ranks(shim):
+    # violations filled in from a neighbour's row of the same 64-rank tile
+    total_borrowed = 0
+    for p in list(range(1, 600)) + [1025, 4097, 65537]:
+        for root in {0, p // 2, p - 1}:
+            rows, flags, _, borrowed = shim_tiles(shim, p, root, 0, p)
+            assert np.array_equal(rows, oracle.schedules(p, root=root, send_mode=1)), (p, root)
+            assert not flags.any()
+            total_borrowed += borrowed
+    assert total_borrowed > 10000
+    for p, root, a, n in [(1000003, 17, 499000, 5000), (2**31 - 1, 99, 2**31 - 5000, 4999),
+                          (3 * 2**28 + 5, 2**29, 2**29 - 1000, 3000), (65537, 65536, 65000, 537)]:
+        rows, flags, _, borrowed = shim_tiles(shim, p, root, a, n)
+        assert np.array_equal(rows, oracle.schedules(p, root=root, r_begin=a, r_end=a + n))
+        assert not flags.any()
 
 
 def test_all_ranks_small_p(shim):

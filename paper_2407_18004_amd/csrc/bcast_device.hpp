@@ -17,6 +17,7 @@
 namespace bcast {
 
 constexpr uint32_t kEndLevel = 0xFFFFFFFFu;
+constexpr uint32_t kLockstepSkip = 1024u;   // see recv_search_fast: where the ascent re-synchronises
 
 // skip[q - j]
 __device__ __forceinline__ uint32_t skip_at_level(uint32_t pm1, uint32_t j) {
@@ -245,28 +246,55 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
   // Ascent.
   const uint32_t k_stop = k_last + 1u < q ? k_last + 1u : q;
   const uint32_t cap = 8u * q + 16u;
+  // The ascent runs as two loops over the same body.  Lanes of a wavefront hold
+  // consecutive ranks: their searches differ in the deep levels (small skips)
+  // and agree, move for move, once those are all accepted.  The first loop
+  // lets every lane finish its deep levels and wait; the second then runs with
+  // all lanes making the same move, so each iteration takes one branch only.
+  uint32_t deep = 0;                        // levels whose skip is below kLockstepSkip
+  if (pm1 >= kLockstepSkip) {
+    const uint32_t first_deep = 32u - (uint32_t)__clz((int)(pm1 / kLockstepSkip));
+    deep = first_deep < 32u ? 0xFFFFFFFFu << first_deep : 0u;
+  } else {
+    deep = 0xFFFFFFFFu;
+  }
   bool go = k < k_stop && !((int)j < 0 && pathr == 0);
-  for (uint32_t it = 0; it < cap && go; ++it) {
-    const bool is_end = (int)j < 0;
-    const uint32_t jp = 31u - (uint32_t)(__ffs((int)pathr) - 1);
-    const uint32_t jj = is_end ? jp : j;
-    const uint32_t a = skip_at_level(pm1, jj);
-    const uint32_t D1 = D + (is_end ? a : 0u);
-    const uint32_t t = D1 - a;
-    const bool pass = !is_end && a <= D1 && t >= M;
-    const bool rec = pass && t >= sk1;
-    const bool post = is_end || (pass && !rec);
-    const bool acc = post && D1 >= sk1;
-    const bool ret = post && D1 < sk1;
-    anom |= (uint32_t)(rec && a <= t && t - a >= M);
-    D = rec ? t : D1;
-    pathr ^= (is_end || rec) ? (0x80000000u >> jj) : 0u;
-    if (acc) {
-      emit(k, jj == 0 ? b : -(int)jj);
-      live ^= 1u << jj;
-      M = sk1 > t + 1u ? sk1 : t + 1u;
-      ++k;
-      sk1 = skip_at_level(pm1, (q - k - 1u) & 31u);       // skip[k+1]; unused once k = q
+  uint32_t it = 0;
+  for (uint32_t phase = 0; phase < 2u; ++phase)
+  for (; it < cap && go && (phase == 1u || (live & deep) != 0u); ++it) {
+    uint32_t jj, a, t;
+    bool post;
+    if ((int)j < 0) {                       // list exhausted: back to the pending call
+      jj = 31u - (uint32_t)(__ffs((int)pathr) - 1);
+      a = skip_at_level(pm1, jj);
+      t = D;                                // D - skip[e] seen from the caller's frame
+      D += a;
+      pathr ^= 0x80000000u >> jj;
+      post = true;
+    } else {
+      jj = j;
+      a = skip_at_level(pm1, jj);
+      t = D - a;
+      const bool pass = a <= D && t >= M;
+      const bool rec = pass && t >= sk1;
+      post = pass && !rec;
+      if (rec) {                            // recursive call on r' + skip[e]
+        anom |= (uint32_t)(a <= t && t - a >= M);
+        D = t;
+        pathr |= 0x80000000u >> jj;
+      }
+    }
+    bool ret = false;
+    if (post) {
+      if (D >= sk1) {                       // accept e for round k
+        emit(k, jj == 0 ? b : -(int)jj);
+        live ^= 1u << jj;
+        M = sk1 > t + 1u ? sk1 : t + 1u;
+        ++k;
+        sk1 = skip_at_level(pm1, (q - k - 1u) & 31u);     // skip[k+1]; unused once k = q
+      } else {
+        ret = true;                         // r' > R - skip[k+1]: this frame returns
+      }
     }
     j = ret ? kEndLevel : next_level(live, jj);
     go = k < k_stop && !((int)j < 0 && pathr == 0);
@@ -300,20 +328,25 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
 }
 
 // Phase two, for tiles of consecutive ranks: a violation in round k needs
-// recvblock[k] of rank r + skip[k]; if that rank sits `skip[k]` lanes further
-// in the same tile its row is already in LDS (row_pitch bytes per lane).
-// Returns the violations that are still open.  Call after the tile's phase one
-// is complete and visible.
-__device__ __forceinline__ uint32_t resolve_from_tile(const Instance &in, uint32_t viol,
-                                                      const int8_t *recv_row, int8_t *send_row,
-                                                      uint32_t row_pitch, uint32_t lane,
-                                                      uint32_t n_valid) {
+// recvblock[k] of rank r + skip[k].  If that rank sits skip[k] lanes further in
+// the same tile, or in the following tile of 64 ranks whose rows are still in
+// LDS, its row is read instead of recomputed.  tile_recv and next_recv point at
+// the receive row of lane 0 of the two tiles (next_recv may be null); rows are
+// row_pitch bytes apart.  Returns the violations that are still open.  Call
+// after phase one of the tile is complete and visible.
+__device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint32_t viol,
+                                                       int8_t *send_row, const int8_t *tile_recv,
+                                                       const int8_t *next_recv, uint32_t row_pitch,
+                                                       uint32_t lane, uint32_t n_valid,
+                                                       uint32_t n_valid_next) {
   uint32_t open = 0;
   while (viol != 0) {
     const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
     viol &= viol - 1u;
-    const uint32_t sk = skip_at_level(in.pm1, in.q - k);
-    if (sk < n_valid && lane < n_valid - sk) send_row[k] = recv_row[sk * row_pitch + k];
+    const uint32_t tl = lane + skip_at_level(in.pm1, in.q - k);   // < 2^32: lane < 64, skip < 2^31
+    if (tl < n_valid) send_row[k] = tile_recv[tl * row_pitch + k];
+    else if (next_recv != nullptr && n_valid == 64u && tl - 64u < n_valid_next)
+      send_row[k] = next_recv[(tl - 64u) * row_pitch + k];
     else open |= 1u << k;
   }
   return open;

@@ -82,22 +82,43 @@ struct SchedParams {
   int layout;
 };
 
+// Wavefront w works through the tiles [w*run, (w+1)*run) from the highest
+// down, keeping the previous (= following in rank order) tile in the other
+// half of its LDS slice: a violation of Algorithm 6 asks for a row of a higher
+// rank, which is then usually still there.
+__device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint64_t &t_hi) {
+  const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+  const uint64_t run = (n_tiles + n_waves - 1) / n_waves;
+  const uint64_t w = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+  t_lo = w * run < n_tiles ? w * run : n_tiles;
+  t_hi = t_lo + run < n_tiles ? t_lo + run : n_tiles;
+}
+
+// LDS of the tiled kernels is sized at launch: per wavefront kNextTile + 1
+// slices of 64 rows of 2q bytes (rounded up to 16 bytes).
+__host__ __device__ inline uint32_t slice_words(uint32_t q) { return ((kWave * 2u * q + 15u) / 16u) * 4u; }
+
+template <bool kNextTile>
 __global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
-  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  constexpr uint32_t kBufs = kNextTile ? 2u : 1u;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
-  int8_t *slice = reinterpret_cast<int8_t *>(lds[wave]);
   // row pitch, and offset of the send part inside the slice
   const uint32_t pitch = prm.layout == kSeparate ? q : 2u * q;
   const uint32_t send_off = prm.layout == kSeparate ? kWave * q : q;
-  int8_t *recv_row = slice + lane * pitch;
-  int8_t *send_row = recv_row + send_off;
 
-  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
-  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
-       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+  uint64_t t_lo, t_hi;
+  tile_run((prm.n_ranks + kWave - 1) / kWave, t_lo, t_hi);
+  uint32_t cur = 0, n_valid_next = 0;
+  const int8_t *next_recv = nullptr;
+  for (uint64_t tile = t_hi; tile-- > t_lo;) {
+    uint32_t *words = lds_dyn + (wave * kBufs + cur) * slice_words(q);
+    int8_t *tile_recv = reinterpret_cast<int8_t *>(words);
+    int8_t *recv_row = tile_recv + lane * pitch;
+    int8_t *send_row = recv_row + send_off;
     const uint64_t row0 = tile * kWave;
     const uint64_t left = prm.n_ranks - row0;
     const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
@@ -111,21 +132,28 @@ __global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
     }
     wave_lds_sync();
     if (lane < n_valid) {
-      viol = resolve_from_tile(in, viol, recv_row, send_row, pitch, lane, n_valid);
+      viol = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, lane, n_valid,
+                                n_valid_next);
       resolve_by_search(in, v, viol, send_row);
     }
     wave_lds_sync();
     if (prm.layout == kInterleaved) {
-      tile_out<false>(lds[wave], prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
+      tile_out<false>(words, prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
     } else if (prm.layout == kSeparate) {
-      tile_out<false>(lds[wave], prm.recv + row0 * q, n_valid * q, lane);
-      tile_out<false>(lds[wave] + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
+      tile_out<false>(words, prm.recv + row0 * q, n_valid * q, lane);
+      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
     } else if (lane < n_valid) {
       int32_t *rr = prm.recv + (row0 + lane) * (uint64_t)prm.ld;
       int32_t *sr = prm.send + (row0 + lane) * (uint64_t)prm.ld;
       for (uint32_t k = 0; k < q; ++k) { rr[k] = recv_row[k]; sr[k] = send_row[k]; }
     }
-    wave_lds_sync();
+    if (kNextTile) {
+      next_recv = tile_recv;
+      n_valid_next = n_valid;
+      cur ^= 1u;
+    } else {
+      wave_lds_sync();                       // the one slice is rewritten next
+    }
   }
 }
 
@@ -142,25 +170,30 @@ __global__ void k_digest_init(uint64_t *digest, uint32_t *flags) {
   if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; }
 }
 
+template <bool kNextTile>
 __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
-  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  constexpr uint32_t kBufs = kNextTile ? 2u : 1u;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
-  int8_t *recv_row = reinterpret_cast<int8_t *>(lds[wave]) + lane * 2u * q;
-  int8_t *send_row = recv_row + q;
 
   uint64_t acc = 0;
   uint32_t acc_flags = 0;
-  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
-  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
-       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
-    const uint64_t row = tile * kWave + lane;
-    const uint64_t left = prm.n_ranks - tile * kWave;
+  uint64_t t_lo, t_hi;
+  tile_run((prm.n_ranks + kWave - 1) / kWave, t_lo, t_hi);
+  uint32_t cur = 0, n_valid_next = 0;
+  const int8_t *next_recv = nullptr;
+  for (uint64_t tile = t_hi; tile-- > t_lo;) {
+    int8_t *tile_recv = reinterpret_cast<int8_t *>(lds_dyn + (wave * kBufs + cur) * slice_words(q));
+    int8_t *recv_row = tile_recv + lane * 2u * q;
+    int8_t *send_row = recv_row + q;
+    const uint64_t row0 = tile * kWave;
+    const uint64_t left = prm.n_ranks - row0;
     const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
     const bool valid = lane < n_valid;
-    const uint32_t r = (uint32_t)(prm.r_begin + row);
+    const uint32_t r = (uint32_t)(prm.r_begin + row0 + lane);
     uint32_t v = 0, viol = 0, fl = 0;
     int b = 0;
     if (valid) {
@@ -169,7 +202,8 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
     }
     wave_lds_sync();
     if (valid) {
-      viol = resolve_from_tile(in, viol, recv_row, send_row, 2u * q, lane, n_valid);
+      viol = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, 2u * q, lane, n_valid,
+                                n_valid_next);
       fl |= resolve_by_search(in, v, viol, send_row);
       uint64_t h;
       uint32_t fl2;
@@ -177,7 +211,13 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
       acc ^= h;
       acc_flags |= fl | fl2;
     }
-    wave_lds_sync();
+    if (kNextTile) {
+      next_recv = tile_recv;
+      n_valid_next = n_valid;
+      cur ^= 1u;
+    } else {
+      wave_lds_sync();                       // the one slice is rewritten next
+    }
   }
   acc = wave_xor64(acc);
   acc_flags = wave_or32(acc_flags);
@@ -406,6 +446,11 @@ int persistent_grid(uint64_t n_blocks_wanted) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// Algorithm 6 has no violations when every skip below p is a power of two
+// (p = 2^q and p = 2^q - 1): no reason then to keep the following tile in LDS.
+// The choice only affects speed; an unexpected violation is resolved by search.
+bool keep_next_tile(uint32_t p) { return (p & (p - 1u)) != 0u && (p & (p + 1u)) != 0u; }
+
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
@@ -457,7 +502,13 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
   const uint64_t blocks = (n + kBlock - 1) / kBlock;
   const int grid = persistent_grid(blocks);
   if (grid < 0) return BCAST_EHIP;
-  hipLaunchKernelGGL(k_schedules, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
+  if (keep_next_tile(p)) {
+    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL(k_schedules<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  } else {
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL(k_schedules<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 
@@ -476,7 +527,13 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   prm.digest = digest; prm.flags = flags;
   const int grid = persistent_grid((n + kBlock - 1) / kBlock);
   if (grid < 0) return BCAST_EHIP;
-  hipLaunchKernelGGL(k_digest, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
+  if (keep_next_tile(p)) {
+    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL(k_digest<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  } else {
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL(k_digest<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 

@@ -48,10 +48,16 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
   uint64_t borrowed = 0;
-  for (uint64_t row0 = 0; row0 < n; row0 += 64) {
+  // tiles from the highest down, two buffers, as a wavefront does within its run
+  static int8_t tiles[2][64 * 62];
+  uint32_t cur = 0, n_valid_next = 0;
+  const int8_t *next_recv = nullptr;
+  const uint64_t n_tiles = (n + 63) / 64;
+  for (uint64_t ti = n_tiles; ti-- > 0;) {
+    const uint64_t row0 = ti * 64;
     const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
-    int8_t tile[64 * 62];
-    memset(tile, 0x55, sizeof tile);
+    int8_t *tile = tiles[cur];
+    memset(tile, 0x55, 64 * 62);
     uint32_t viol[64], fl[64], vr[64];
     int b[64];
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
@@ -61,8 +67,8 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     }
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
       int8_t *recv_row = tile + lane * 2 * q;
-      const uint32_t open = resolve_from_tile(in, viol[lane], recv_row, recv_row + q, 2 * q,
-                                              lane, n_valid);
+      const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
+                                               2 * q, lane, n_valid, n_valid_next);
       borrowed += (uint64_t)__popc(viol[lane] ^ open);
       fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
     }
@@ -76,6 +82,9 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
       if (flags_out) flags_out[i] = fl[lane] | fl2;
       if (hash_out) hash_out[i] = h;
     }
+    next_recv = tile;
+    n_valid_next = n_valid;
+    cur ^= 1u;
   }
   if (n_from_tile) *n_from_tile = borrowed;
   return (int)q;

@@ -33,22 +33,16 @@ PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 PEAK_HBM = 8.0e12
 
 
-def lane_ops_per_rank(q: int) -> float:
-    """Algorithmic 32-bit lane-operations of one rank-schedule in digest mode.
-
-    Counted from the straight-line per-rank algorithm as this library states it
-    (one operation = one 32-bit integer instruction of one lane; a 64-bit
-    multiply of the hash counts as its four 32-bit multiplies plus adds):
-      baseblock walk      6 per level, q levels
-      receive search      24 per step of the state machine, 2.2 q steps on average
-                          (scans of Algorithm 4 measured with the oracle's counters)
-      send walk           16 per round, q rounds
-      flags + packing     17 per entry, 2q entries
-      hash                44 per SplitMix64 call, 1 + ceil(2q / 10) calls
-    Violations (rare at p = 2^31 - 1) are not counted.
-    """
-    calls = 1 + (2 * q + 9) // 10
-    return 6.0 * q + 24.0 * 2.2 * q + 16.0 * q + 17.0 * 2 * q + 44.0 * calls
+def load_counters() -> dict:
+    """Per-kernel figures taken from rocprofv3 counters (profiles/bench_counters.json, which
+    names the summaries it was computed from): active VALU lane-operations per rank-schedule
+    and HBM bytes per launch.  Empty if the file is missing."""
+    path = os.path.join(ROOT, "profiles", "bench_counters.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get("kernels", {})
+    except (OSError, ValueError):
+        return {}
 
 
 def run(args) -> dict:
@@ -83,6 +77,14 @@ def run(args) -> dict:
                 e1.record()
                 events.append((e0, e1))
 
+    if args.copy_probe:                 # known traffic: 256 MiB read + 256 MiB written per copy
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -103,14 +105,20 @@ def run(args) -> dict:
     launch_ms = [a.elapsed_time(b) for a, b in events]
     avg_launch_ms = sum(launch_ms) / len(launch_ms)
     ranks_per_launch = p / n_chunks
-    achieved = lane_ops_per_rank(q) * ranks_per_launch / (avg_launch_ms * 1e-3)
+    # Work per rank-schedule = the 32-bit integer lane-operations this kernel's active lanes
+    # execute for one rank (SQ_THREAD_CYCLES_VALU / ranks, measured once with rocprofv3);
+    # achieved = that figure x ranks per launch / live launch duration.
+    counters = load_counters()
+    ops = counters.get("k_digest", {}).get("active_valu_lane_ops_per_rank")
+    achieved = ops * ranks_per_launch / (avg_launch_ms * 1e-3) if ops else None
     roofline = {
         "kernel": "k_digest", "bound": "alu",
-        "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-        "frac": achieved / PEAK_LANE_OPS,
-        "traffic": load_traffic("k_digest"),
+        "achieved": achieved / 1e12 if achieved else None,
+        "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+        "frac": achieved / PEAK_LANE_OPS if achieved else None,
+        "traffic": counters.get("k_digest", {}).get("hbm_bytes_per_launch"),
         "avg_launch_ms": avg_launch_ms, "launches": len(launch_ms),
-        "lane_ops_per_rank": lane_ops_per_rank(q),
+        "lane_ops_per_rank": ops,
     }
 
     out = {
@@ -123,14 +131,14 @@ def run(args) -> dict:
                    "p": p, "q": q, "chunks": n_chunks, "digest": f"{whole:016x}",
                    "flags": flags_or},
         "roofline": roofline,
-        "materialised": bench_materialised(torch, lib, workloads, dev, args),
+        "materialised": bench_materialised(torch, lib, workloads, dev, args, counters),
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(p, whole_digest=None)
     return out
 
 
-def bench_materialised(torch, lib, workloads, dev, args) -> dict:
+def bench_materialised(torch, lib, workloads, dev, args, counters) -> dict:
     """The [p][2q] table of p = 1,000,003 (q = 20): 8q bytes written per rank."""
     p = workloads.MATERIALISED_P
     q = lib.bcast_q(p)
@@ -158,18 +166,8 @@ def bench_materialised(torch, lib, workloads, dev, args) -> dict:
         "roofline": {"bound": "hbm", "achieved": nbytes / (med * 1e-3) / 1e9,
                      "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                      "frac": nbytes / (med * 1e-3) / PEAK_HBM,
-                     "traffic": load_traffic("k_schedules")},
+                     "traffic": counters.get("k_schedules", {}).get("hbm_bytes_per_launch")},
     }
-
-
-def load_traffic(kernel: str):
-    """HBM bytes per launch from the committed counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    try:
-        with open(path) as fh:
-            return json.load(fh).get(kernel)
-    except (OSError, ValueError):
-        return None
 
 
 def cpu_baseline(p: int, whole_digest=None) -> dict:
@@ -195,6 +193,8 @@ def main() -> None:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (scale for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (rank-schedules are independent; "

@@ -215,21 +215,23 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
   // j at bit 31 - j, so that the deepest one is the lowest set bit.
   int W = (int)((is_root ? p : v) - 2u);
   uint32_t pathr = is_root ? 0u : 0x80000000u;
-  uint32_t jd = 0;
   uint32_t anom = 0;
   for (uint32_t j = 1; j <= q; ++j) {
     const int sk = (int)skip_at_level(pm1, j);           // uniform: scalar
     const int t = W - sk;
     const bool take = j != jb && t >= -1;                 // push (t >= 0) or accept (t = -1)
-    const bool push = take && t >= 0;
-    // the call made for this index would look at the index again
-    // (skip + 1 <= D - skip): that look never passes
-    anom |= (uint32_t)(push && sk <= t + 1);
-    jd = (take && !push) ? j : jd;
+    // The call made for this index would look at the index again (skip + 1 <=
+    // D - skip) and that look must fail.  It does whenever the level above was
+    // looked at (skip[e+1] <= 2 skip[e]); only right below the baseblock's
+    // level, which is not in the list, the test is made explicitly.
+    if (__any(j == jb + 1u)) anom |= (uint32_t)(j == jb + 1u && take && t >= 0 && sk <= t + 1);
     W = take ? t : W;
-    pathr |= push ? (0x80000000u >> j) : 0u;
+    pathr |= take ? (0x80000000u >> j) : 0u;              // the accepted level too, for now
   }
   const bool hit = W == -1;
+  // The accept, if any, was the last level taken: the deepest bit of pathr.
+  const uint32_t jd = hit ? 31u - (uint32_t)(__ffs((int)pathr) - 1) : 0u;
+  pathr = hit ? pathr & (pathr - 1u) : pathr;
   uint32_t live = (q >= 31 ? 0xFFFFFFFFu : ((2u << q) - 1u)) & ~(1u << jb);
   uint32_t D = hit ? (uint32_t)skip_at_level(pm1, jd) + 1u : (uint32_t)(W + 2);
   uint32_t k = 0, j = kEndLevel;

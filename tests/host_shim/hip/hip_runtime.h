@@ -11,5 +11,6 @@
 static inline int __ffs(int x) { return x == 0 ? 0 : __builtin_ctz((unsigned)x) + 1; }
 static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
 static inline int __popc(unsigned x) { return __builtin_popcount(x); }
-// cross-lane operations have no meaning for a single lane
+// cross-lane operations for a wavefront of one lane
+static inline int __any(int pred) { return pred != 0; }
 static inline int __shfl_xor(int v, int, int) { return v; }

@@ -132,6 +132,7 @@ def run(args) -> dict:
                    "flags": flags_or},
         "roofline": roofline,
         "materialised": bench_materialised(torch, lib, workloads, dev, args, counters),
+        "other_workloads": bench_other(torch, lib, workloads, dev),
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(p, whole_digest=None)
@@ -167,6 +168,60 @@ def bench_materialised(torch, lib, workloads, dev, args, counters) -> dict:
                      "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                      "frac": nbytes / (med * 1e-3) / PEAK_HBM,
                      "traffic": counters.get("k_schedules", {}).get("hbm_bytes_per_launch")},
+    }
+
+
+def _median_ms(torch, fn, reps: int) -> float:
+    fn()
+    torch.cuda.synchronize()
+    evs = []
+    for _ in range(reps):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return ms[len(ms) // 2]
+
+
+def bench_other(torch, lib, workloads, dev) -> dict:
+    """Context figures for the two workloads that are not rank ranges: an eighth of the
+    batched instances (8,192 x 4,096 ranks, packed rows) and the broadcast replay."""
+    import numpy as np
+    from paper_2407_18004_amd.binding import VERDICT_BYTES
+    n_inst, m = 8192, 4096
+    p, root, ranks = workloads.batched_instances(n_inst, m, seed=42)
+    row_off = workloads.batched_row_offsets(p, m)
+    d = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a).view(dt)).to(dev)  # noqa: E731
+    dp, droot, dranks, doff = d(p, np.int32), d(root, np.int32), d(ranks, np.int32), d(row_off, np.int64)
+    out = torch.empty(int(row_off[-1]), dtype=torch.int32, device=dev)
+    rej = torch.zeros(1, dtype=torch.int32, device=dev)
+    ms_b = _median_ms(torch, lambda: lib.bcast_schedules_batched(n_inst, dp, droot, dranks, m, doff,
+                                                                 out, rej), 5)
+    assert int(rej.item()) == 0
+    nbytes = 4.0 * int(row_off[-1]) + 4.0 * n_inst * m
+    del out
+    ps, n = workloads.SIMULATION_P, workloads.SIMULATION_N
+    roots = workloads.simulation_roots(64, seed=42)
+    q = lib.bcast_q(ps)
+    ws = torch.empty(lib.bcast_simulate_workspace(ps, n, 64), dtype=torch.uint8, device=dev)
+    vd = torch.zeros(64 * VERDICT_BYTES, dtype=torch.uint8, device=dev)
+    ms_1 = _median_ms(torch, lambda: lib.bcast_simulate(ps, n, [workloads.SIMULATION_ROOT], None,
+                                                        ws, vd), 5)
+    ms_64 = _median_ms(torch, lambda: lib.bcast_simulate(ps, n, roots, None, ws, vd), 5)
+    rounds = n - 1 + q
+    return {
+        "batched": {"workload": "8192 seeded instances x 4096 ranks (an eighth of workload 4)",
+                    "kernel": "k_batched", "median_launch_ms": ms_b,
+                    "rank_schedules_per_s": n_inst * m / (ms_b * 1e-3),
+                    "hbm_GB_per_s": nbytes / (ms_b * 1e-3) / 1e9},
+        "simulate": {"workload": "p=65537 n=256 (272 rounds), schedules computed in the call",
+                     "kernel": "k_schedules + k_simulate",
+                     "one_root_ms": ms_1, "64_roots_ms": ms_64,
+                     "processor_rounds_per_s_64_roots": 64.0 * ps * rounds / (ms_64 * 1e-3)},
     }
 
 

@@ -80,6 +80,11 @@ def _load():
                  "orc_schedules_ranks", "orc_digest", "orc_digest_row",
                  "orc_simulate"):
         getattr(lib, name).restype = ctypes.c_int
+    u64p = ctypes.POINTER(ctypes.c_uint64)
+    lib.orc_edgecheck.argtypes = [i64, i64, i64, i64, u64p, u64p, ctypes.c_int, ctypes.c_int]
+    lib.orc_edgecheck.restype = ctypes.c_int
+    lib.orc_edgecheck_table.argtypes = [i64, i32p, u64p, u64p]
+    lib.orc_edgecheck_table.restype = ctypes.c_int
     lib.orc_sm64.argtypes = [ctypes.c_uint64]
     lib.orc_sm64.restype = ctypes.c_uint64
     _lib = lib
@@ -218,6 +223,29 @@ def digest_row(p: int, root: int, r: int, recv, send, viol_count: int = 0,
                                   _i32p(send if q else pad), viol_count, produced,
                                   ctypes.byref(h), ctypes.byref(fl)), "orc_digest_row")
     return int(h.value), int(fl.value)
+
+
+def edgecheck(p: int, root: int, r_begin: int, r_end: int, send_mode: int = 1,
+              threads: int | None = None) -> tuple[int, int]:
+    """(xor_recv, xor_send) of the edge check over physical ranks [r_begin, r_end)."""
+    xr, xs = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    if threads is None:
+        threads = default_threads()
+    _check(_load().orc_edgecheck(p, root, r_begin, r_end, ctypes.byref(xr), ctypes.byref(xs),
+                                 send_mode, threads), "orc_edgecheck")
+    return int(xr.value), int(xs.value)
+
+
+def edgecheck_table(p: int, sched: np.ndarray) -> tuple[int, int]:
+    """(xor_recv, xor_send) of a given table sched[p][2q]."""
+    q = q_of(p)
+    sched = np.ascontiguousarray(sched, dtype=np.int32)
+    assert sched.shape == (p, 2 * q)
+    xr, xs = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    pad = np.zeros(1, dtype=np.int32)
+    _check(_load().orc_edgecheck_table(p, _i32p(sched if sched.size else pad), ctypes.byref(xr),
+                                       ctypes.byref(xs)), "orc_edgecheck_table")
+    return int(xr.value), int(xs.value)
 
 
 def simulate(p: int, n: int, root: int = 0, sched: np.ndarray | None = None) -> dict:

@@ -443,6 +443,63 @@ int orc_digest(int64_t p, int64_t root, int64_t r_begin, int64_t r_end,
     return q;
 }
 
+/* --------------------------------------------------------- edge check ---- */
+
+static uint64_t edge_hash(int64_t rank, int k, int32_t val)
+{
+    return sm64(((uint64_t)rank << 11) | ((uint64_t)k << 6) | ((uint64_t)(val + 32) & 63u));
+}
+
+static void edge_row(const int64_t *skip, int q, int64_t p, int64_t r, const int32_t *recv,
+                     const int32_t *send, uint64_t *xr, uint64_t *xs)
+{
+    for (int k = 0; k < q; k++) {
+        int64_t t = (r + skip[k]) % p;              /* to-processor of physical rank r */
+        *xr ^= edge_hash(r, k, recv[k]);
+        *xs ^= edge_hash(t, k, send[k]);
+    }
+}
+
+int orc_edgecheck(int64_t p, int64_t root, int64_t r_begin, int64_t r_end,
+                  uint64_t *xor_recv, uint64_t *xor_send, int send_mode, int threads)
+{
+    int64_t skip[ORC_MAXQ + 2];
+    int q = orc_skips(p, skip);
+    if (q < 0 || q > 31 || root < 0 || root >= p || r_begin < 0 || r_begin > r_end || r_end > p)
+        return -1;
+    skip[q + 1] = 0;
+    uint64_t xr = 0, xs = 0;
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static, 4096) reduction(^ : xr, xs) \
+    num_threads(threads > 1 ? threads : 1)
+#endif
+    for (int64_t r = r_begin; r < r_end; r++) {
+        int32_t recv[ORC_MAXQ + 1], send[ORC_MAXQ + 1];
+        int64_t v = virtual_rank(r, root, p);
+        recvschedule_sk(skip, q, p, v, recv, NULL);
+        if (send_mode == 0) sendschedule_def_sk(skip, q, p, v, send);
+        else sendschedule_sk(skip, q, p, v, send, NULL, NULL);
+        edge_row(skip, q, p, r, recv, send, &xr, &xs);
+    }
+    *xor_recv = xr;
+    *xor_send = xs;
+    return q;
+}
+
+int orc_edgecheck_table(int64_t p, const int32_t *sched, uint64_t *xor_recv, uint64_t *xor_send)
+{
+    int64_t skip[ORC_MAXQ + 2];
+    int q = orc_skips(p, skip);
+    if (q < 0 || q > 31 || !sched) return -1;
+    uint64_t xr = 0, xs = 0;
+    for (int64_t r = 0; r < p; r++)
+        edge_row(skip, q, p, r, sched + r * 2 * q, sched + r * 2 * q + q, &xr, &xs);
+    *xor_recv = xr;
+    *xor_send = xs;
+    return q;
+}
+
 /* ---------------------------------------------------------- simulator ---- */
 
 static void note_bad(orc_verdict *vd, int64_t round, int64_t rank)

@@ -122,6 +122,20 @@ int orc_digest_row(int64_t p, int64_t root, int64_t r, const int32_t *recv,
                    const int32_t *send, int viol_count, int produced,
                    uint64_t *hash, uint32_t *flags);
 
+/* Conditions 1 and 2 over a rank range without a table (a definition of this
+ * build).  Every rank r contributes, for each round k,
+ *     xor_recv ^= g(r, k, recv[k]_r)      what r expects to receive in round k
+ *     xor_send ^= g(t, k, send[k]_r)      what r sends to t = (r + skip[k]) mod p
+ * with g(rank, k, val) = sm64(rank << 11 | k << 6 | (val + 32)).  Over ALL ranks
+ * of an instance the two multisets of (rank, k, block) triples are equal exactly
+ * when every receive entry matches the send entry of its from-processor, so
+ * the two XORs must then be equal; ranges combine by XOR. */
+int orc_edgecheck(int64_t p, int64_t root, int64_t r_begin, int64_t r_end,
+                  uint64_t *xor_recv, uint64_t *xor_send, int send_mode, int threads);
+
+/* The same two XORs of a given table sched[p][2q] (all ranks, physical order). */
+int orc_edgecheck_table(int64_t p, const int32_t *sched, uint64_t *xor_recv, uint64_t *xor_send);
+
 /* Algorithm 1 with possession marks instead of payload: n blocks, root,
  * schedules sched[r*2q + k] = recv, sched[r*2q + q + k] = send for physical
  * rank r (raw entries, not yet shifted by x); sched == NULL recomputes them

@@ -351,6 +351,10 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
       const int64_t nm1 = (int64_t)n - 1;
       uint32_t k = prm.x % q;
       int64_t shift = -(int64_t)prm.x + (int64_t)q * (prm.x / q);
+      // The word of the possession column that was written last stays in a
+      // register: blocks arrive in nearly increasing order, so a word serves
+      // some 32 rounds before the next one is fetched.
+      uint32_t cw = 0xFFFFFFFFu, cv = 0u;
       for (uint32_t round = 0; round < prm.rounds; ++round) {
         int64_t rb = (int64_t)st_recv[k][lane_b] + shift;
         int64_t fb = (int64_t)st_from[k][lane_b] + shift;
@@ -367,25 +371,31 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
         const bool to_root = v + sk == p;
         if (sb >= 0 && !to_root) {                  // state before this round
           sb = sb > nm1 ? nm1 : sb;
-          const uint32_t word = col[(uint64_t)((uint32_t)sb >> 5) * p];
+          const uint32_t w = (uint32_t)sb >> 5;
+          const uint32_t word = w == cw ? cv : col[(uint64_t)w * p];
           if (((word >> ((uint32_t)sb & 31u)) & 1u) == 0) {
             ++n_unheld;
             first_bad = key < first_bad ? key : first_bad;
           }
         }
         if (has_r) {
-          uint32_t *wp = col + (uint64_t)((uint32_t)rb >> 5) * p;
-          const uint32_t word = *wp;
+          const uint32_t w = (uint32_t)rb >> 5;
+          if (w != cw) {
+            if (cw != 0xFFFFFFFFu) col[(uint64_t)cw * p] = cv;
+            cw = w;
+            cv = col[(uint64_t)w * p];
+          }
           const uint32_t bit = 1u << ((uint32_t)rb & 31u);
-          if (word & bit) {
+          if (cv & bit) {
             ++n_dup;
             first_bad = key < first_bad ? key : first_bad;
           } else {
-            *wp = word | bit;
+            cv |= bit;
           }
         }
         if (++k == q) { k = 0; shift += q; }
       }
+      if (cw != 0xFFFFFFFFu) col[(uint64_t)cw * p] = cv;
       uint32_t have = 0;
       for (uint32_t w = 0; w < prm.n_words; ++w) {
         uint32_t word = col[(uint64_t)w * p];

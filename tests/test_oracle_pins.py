@@ -506,3 +506,36 @@ def test_digest_known_answers():
     for it in items:
         dg, fl = oracle.digest(it["p"], it["root"], it["r_begin"], it["r_end"])
         assert (dg, fl) == (int(it["digest"], 16), it["flags"]), it
+
+
+# ---------------------------------------------------------- edge check ----
+
+def test_edgecheck_is_equal_exactly_when_conditions_1_and_2_hold():
+    # valid schedules: the XOR over what is expected equals the XOR over what is sent
+    for p in list(range(1, 200)) + [1000, 4096, 65537]:
+        for root in {0, p // 2}:
+            xr, xs = oracle.edgecheck(p, root, 0, p)
+            assert xr == xs, (p, root)
+            cut = p // 3                      # ranges combine by XOR
+            a, b = oracle.edgecheck(p, root, 0, cut), oracle.edgecheck(p, root, cut, p)
+            assert (a[0] ^ b[0], a[1] ^ b[1]) == (xr, xs)
+        if p > 2:
+            part = oracle.edgecheck(p, 0, 0, p - 1)
+            assert part[0] != part[1]         # the identity needs all ranks
+    # a table with one wrong entry breaks Condition 1 on one edge and the equality with it
+    p = 1000
+    q = oracle.q_of(p)
+    good = oracle.schedules(p)
+    assert oracle.edgecheck_table(p, good) == oracle.edgecheck(p, 0, 0, p)
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        bad = good.copy()
+        r, c = int(rng.integers(0, p)), int(rng.integers(0, 2 * q))
+        bad[r, c] = bad[r, c] + 1 if bad[r, c] < q - 1 else bad[r, c] - 1
+        xr, xs = oracle.edgecheck_table(p, bad)
+        assert xr != xs
+    # swapping the send rows of two ranks keeps each row plausible but breaks edges
+    bad = good.copy()
+    bad[[10, 500], q:] = good[[500, 10], q:]
+    xr, xs = oracle.edgecheck_table(p, bad)
+    assert xr != xs

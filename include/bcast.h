@@ -108,6 +108,20 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin,
                            uint64_t r_end, uint64_t *digest, uint32_t *flags,
                            void *stream);
 
+/* Conditions 1 and 2 (every receive entry equals the send entry of its
+ * from-processor) for rank ranges too large to materialise.  For each rank r of
+ * the range and each round k, with g(rank, k, val) = sm64(rank << 11 | k << 6 |
+ * (val + 32)):
+ *     xors[0] ^= g(r, k, recv[k]_r)                       what r expects in round k
+ *     xors[1] ^= g((r + skip[k]) mod p, k, send[k]_r)     what r sends, filed under its to-processor
+ * xors (device, two uint64) is overwritten.  Results of disjoint ranges combine
+ * by XOR; once they cover all p ranks of an instance, xors[0] == xors[1] holds
+ * exactly when the two multisets of (rank, round, block) triples agree, i.e.
+ * when both conditions hold on every edge (up to a 2^-64 hash collision).
+ * Errors as for bcast_schedules_digest. */
+int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin,
+                              uint64_t r_end, uint64_t *xors, void *stream);
+
 /* Many instances at once: instance i has p[i] processors, root[i], and asks for
  * the m physical ranks ranks[i*m .. i*m+m).  Row j of instance i, 2*q(p[i])
  * int32 {recv[0..q-1], send[0..q-1]}, is written at

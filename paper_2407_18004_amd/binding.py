@@ -71,6 +71,8 @@ def load_library():
     lib.bcast_skips.argtypes = [u32, ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_int)]
     lib.bcast_schedules.argtypes = [u32, u32, u64, u64, vp, vp, i64, vp]
     lib.bcast_schedules_digest.argtypes = [u32, u32, u64, u64, vp, vp, vp]
+    lib.bcast_schedules_edgecheck.argtypes = [u32, u32, u64, u64, vp, vp]
+    lib.bcast_schedules_edgecheck.restype = ctypes.c_int
     lib.bcast_schedules_batched.argtypes = [u32, vp, vp, vp, u32, vp, vp, u64, vp, vp]
     lib.bcast_simulate_workspace.argtypes = [u32, u32, u32]
     lib.bcast_simulate_workspace.restype = ctypes.c_size_t
@@ -149,6 +151,17 @@ def bcast_schedules_digest(p: int, root: int, r_begin: int, r_end: int, digest, 
         p, root, r_begin, r_end, _dev_ptr(digest, torch.int64, "digest"),
         _dev_ptr(flags, torch.int32, "flags"), _stream_handle(stream)),
         "bcast_schedules_digest")
+
+
+def bcast_schedules_edgecheck(p: int, root: int, r_begin: int, r_end: int, xors,
+                              stream=None) -> None:
+    """xors: device int64 tensor of 2 elements (read them as unsigned)."""
+    import torch
+    if xors is not None and xors.numel() < 2:
+        raise TypeError("xors: two elements are written")
+    _check(load_library().bcast_schedules_edgecheck(
+        p, root, r_begin, r_end, _dev_ptr(xors, torch.int64, "xors"), _stream_handle(stream)),
+        "bcast_schedules_edgecheck")
 
 
 def bcast_schedules_batched(n_inst: int, p, root, ranks, m: int, row_off, out,

@@ -431,6 +431,23 @@ __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint
   hash = h;
 }
 
+// Edge check of one rank (Conditions 1 and 2 as two XOR sums): what physical
+// rank r expects to receive in round k, and what it sends to (r + skip[k]) mod p.
+// g(rank, k, val) = sm64(rank << 11 | k << 6 | (val + 32)); row as in digest_rank.
+__device__ __forceinline__ void edge_rank(const Instance &in, uint32_t r, const int8_t *row,
+                                          uint64_t &xor_recv, uint64_t &xor_send) {
+  const uint32_t q = in.q;
+  for (uint32_t k = 0; k < q; ++k) {
+    const uint32_t sk = skip_at_level(in.pm1, q - k);
+    uint32_t t = r + sk;                               // < 2^32
+    t = t >= in.p ? t - in.p : t;
+    const uint64_t fr = (uint64_t)(((uint32_t)(int)row[k] + 32u) & 63u);
+    const uint64_t fs = (uint64_t)(((uint32_t)(int)row[q + k] + 32u) & 63u);
+    xor_recv ^= sm64(((uint64_t)r << 11) | ((uint64_t)k << 6) | fr);
+    xor_send ^= sm64(((uint64_t)t << 11) | ((uint64_t)k << 6) | fs);
+  }
+}
+
 __device__ __forceinline__ uint64_t wave_xor64(uint64_t x) {
   uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
 #pragma unroll

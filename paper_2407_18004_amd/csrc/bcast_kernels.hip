@@ -170,7 +170,13 @@ __global__ void k_digest_init(uint64_t *digest, uint32_t *flags) {
   if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; }
 }
 
-template <bool kNextTile>
+__global__ void k_edges_init(uint64_t *xors) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { xors[0] = 0; xors[1] = 0; }
+}
+
+// kEdges = false: digest and flags.  kEdges = true: the two XOR sums of the
+// edge check go to prm.digest[0] and prm.digest[1]; flags are not touched.
+template <bool kNextTile, bool kEdges>
 __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   constexpr uint32_t kBufs = kNextTile ? 2u : 1u;
@@ -179,7 +185,7 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
 
-  uint64_t acc = 0;
+  uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
   uint64_t t_lo, t_hi;
   tile_run((prm.n_ranks + kWave - 1) / kWave, t_lo, t_hi);
@@ -205,11 +211,15 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
       viol = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, 2u * q, lane, n_valid,
                                 n_valid_next);
       fl |= resolve_by_search(in, v, viol, send_row);
-      uint64_t h;
-      uint32_t fl2;
-      digest_rank(in, r, v, b, recv_row, h, fl2);
-      acc ^= h;
-      acc_flags |= fl | fl2;
+      if (kEdges) {
+        edge_rank(in, r, recv_row, acc, acc2);
+      } else {
+        uint64_t h;
+        uint32_t fl2;
+        digest_rank(in, r, v, b, recv_row, h, fl2);
+        acc ^= h;
+        acc_flags |= fl | fl2;
+      }
     }
     if (kNextTile) {
       next_recv = tile_recv;
@@ -220,10 +230,12 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
     }
   }
   acc = wave_xor64(acc);
+  if (kEdges) acc2 = wave_xor64(acc2);
   acc_flags = wave_or32(acc_flags);
   if (lane == 0) {
     atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
-    if (acc_flags) atomicOr(prm.flags, acc_flags);
+    if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
+    else if (acc_flags) atomicOr(prm.flags, acc_flags);
   }
 }
 
@@ -543,10 +555,34 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
     const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
-    hipLaunchKernelGGL(k_digest<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
-    hipLaunchKernelGGL(k_digest<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    hipLaunchKernelGGL((k_digest<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  }
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                              uint64_t *xors, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !xors) return BCAST_EINVAL;
+  hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, (hipStream_t)stream, xors);
+  if (!launch_ok()) return BCAST_EHIP;
+  const uint64_t n = r_end - r_begin;
+  if (n == 0 || q == 0) return BCAST_OK;
+  DigestParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
+  prm.r_begin = r_begin; prm.n_ranks = n;
+  prm.digest = xors; prm.flags = nullptr;
+  const int grid = persistent_grid((n + kBlock - 1) / kBlock);
+  if (grid < 0) return BCAST_EHIP;
+  if (keep_next_tile(p)) {
+    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  } else {
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }

@@ -90,6 +90,16 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   return (int)q;
 }
 
+// the two XOR contributions of one row to the edge check
+void shim_edge_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row, uint64_t *xr,
+                   uint64_t *xs) {
+  const uint32_t q = q_of(p);
+  const Instance in = make_instance(p, q, root);
+  int8_t buf[64];
+  for (uint32_t k = 0; k < 2 * q; ++k) buf[k] = (int8_t)row[k];
+  edge_rank(in, r, buf, *xr, *xs);
+}
+
 // flags and hash of a row given by the caller (for planted mistakes)
 void shim_digest_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row,
                      uint64_t *hash, uint32_t *flags) {

@@ -31,6 +31,9 @@ def shim():
     lib.shim_digest_row.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_digest_row.restype = None
+    lib.shim_edge_row.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.shim_edge_row.restype = None
     lib.shim_schedules_tiles.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                          ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
@@ -122,3 +125,19 @@ def test_flags_on_planted_mistakes(shim):
             bad = np.ascontiguousarray(bad, dtype=np.int32)
             shim.shim_digest_row(p, root, r, bad.ctypes.data, ctypes.byref(h), ctypes.byref(fl))
             assert (int(h.value), int(fl.value)) == want, (r, pos, bad.tolist())
+
+
+def test_edge_check_rows(shim):
+    for p, root in [(17, 0), (1000, 321), (65537, 65536), (2**31 - 1, 12345)]:
+        rng = np.random.default_rng(p)
+        ranks = rng.integers(0, p, size=300).astype(np.uint32)
+        rows = oracle.schedules_ranks(p, root, ranks)
+        xr, xs = ctypes.c_uint64(0), ctypes.c_uint64(0)
+        want_r = want_s = 0
+        for j, r in enumerate(ranks):
+            row = np.ascontiguousarray(rows[j])
+            shim.shim_edge_row(p, root, int(r), row.ctypes.data, ctypes.byref(xr), ctypes.byref(xs))
+            a, b = oracle.edgecheck(p, root, int(r), int(r) + 1)
+            want_r ^= a
+            want_s ^= b
+        assert (int(xr.value), int(xs.value)) == (want_r, want_s)

@@ -47,6 +47,14 @@ def gpu_digest(p, root, a, b):
     return int(dg.item()) & oracle.U64_MAX, int(fl.item()) & 0xFFFFFFFF
 
 
+def gpu_edgecheck(p, root, a, b):
+    x = torch.full((2,), -1, dtype=torch.int64, device=DEV)
+    lib.bcast_schedules_edgecheck(p, root, a, b, x)
+    torch.cuda.synchronize()
+    xr, xs = (int(t) & oracle.U64_MAX for t in x.cpu().tolist())
+    return xr, xs
+
+
 def gpu_simulate(p, n, roots, sched=None):
     ws = torch.empty(lib.bcast_simulate_workspace(p, n, len(roots)), dtype=torch.uint8, device=DEV)
     vd = torch.full((len(roots) * VERDICT_BYTES,), 0xAB, dtype=torch.uint8, device=DEV)
@@ -214,6 +222,31 @@ def test_workload3_seeded_rank_sample_against_definition():
     assert np.array_equal(got, want)
     sub = ranks[:: 16]                      # send by definition (q recv searches per rank)
     assert np.array_equal(got[:: 16], oracle.schedules_ranks(p, 0, sub, send_mode=0))
+
+
+def test_edge_check_matches_oracle_and_holds_on_whole_instances():
+    for p, root, a, b in [(1000, 0, 0, 1000), (1000, 77, 100, 901), (65537, 12345, 0, 65537),
+                          (1, 0, 0, 1), (2, 1, 0, 2), (1000003, 5, 400000, 600001),
+                          (2**31 - 1, 0, 2**31 - 1 - 2**20, 2**31 - 1), (2**30 + 1, 9, 0, 2**20)]:
+        assert gpu_edgecheck(p, root, a, b) == oracle.edgecheck(p, root, a, b), (p, root, a, b)
+    for p, root in [(1000, 0), (65537, 12345), (1000003, 0), (2**24 + 1, 3)]:
+        xr, xs = gpu_edgecheck(p, root, 0, p)
+        assert xr == xs, (p, root)
+        xr, xs = gpu_edgecheck(p, root, 0, p - 1)
+        assert xr != xs
+
+
+def test_workload3_edge_check_of_the_whole_instance():
+    # Conditions 1 and 2 on all 31 * (2^31 - 1) edges, chunk by chunk
+    p = workloads.STREAMED_P
+    xr = xs = 0
+    for a, b in workloads.streamed_chunks():
+        r, s = gpu_edgecheck(p, 0, a, b)
+        xr ^= r
+        xs ^= s
+    assert xr == xs
+    w = 1 << 21
+    assert gpu_edgecheck(p, 0, 2**30 - w, 2**30 + w) == oracle.edgecheck(p, 0, 2**30 - w, 2**30 + w)
 
 
 # ------------------------------------------- workload 4: batched instances --

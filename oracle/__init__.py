@@ -75,6 +75,8 @@ def _load():
                                    ctypes.c_int, ctypes.POINTER(ctypes.c_uint64),
                                    ctypes.POINTER(ctypes.c_uint32)]
     lib.orc_simulate.argtypes = [i64, i64, i64, i32p, ctypes.POINTER(Verdict)]
+    lib.orc_simulate_reduce.argtypes = [i64, i64, i64, i32p, ctypes.POINTER(Verdict)]
+    lib.orc_simulate_reduce.restype = ctypes.c_int
     for name in ("orc_q", "orc_skips", "orc_baseblock", "orc_recvschedule",
                  "orc_sendschedule_def", "orc_sendschedule", "orc_schedules",
                  "orc_schedules_ranks", "orc_digest", "orc_digest_row",
@@ -248,7 +250,13 @@ def edgecheck_table(p: int, sched: np.ndarray) -> tuple[int, int]:
     return int(xr.value), int(xs.value)
 
 
-def simulate(p: int, n: int, root: int = 0, sched: np.ndarray | None = None) -> dict:
+def simulate_reduce(p: int, n: int, root: int = 0, sched: np.ndarray | None = None) -> dict:
+    """The rounds of Algorithm 1 backwards (reduction to the root); verdict as a dict."""
+    return simulate(p, n, root, sched, _fn="orc_simulate_reduce")
+
+
+def simulate(p: int, n: int, root: int = 0, sched: np.ndarray | None = None,
+             _fn: str = "orc_simulate") -> dict:
     """Algorithm 1 over possession marks; returns the verdict as a dict."""
     vd = Verdict()
     ptr = None
@@ -257,5 +265,5 @@ def simulate(p: int, n: int, root: int = 0, sched: np.ndarray | None = None) -> 
         sched = np.ascontiguousarray(sched, dtype=np.int32)
         assert sched.shape == (p, 2 * q)
         ptr = _i32p(sched) if sched.size else None
-    _check(_load().orc_simulate(p, n, root, ptr, ctypes.byref(vd)), "orc_simulate")
+    _check(getattr(_load(), _fn)(p, n, root, ptr, ctypes.byref(vd)), _fn)
     return vd.as_dict()

@@ -602,3 +602,95 @@ int orc_simulate(int64_t p, int64_t n, int64_t root, const int32_t *sched,
     free(vs); free(held); free(mark_v); free(mark_b);
     return 0;
 }
+
+/* Reduction by running the broadcast backwards (Section 2, the observation on
+ * reduction): rounds from the last down to round x, all communication
+ * reversed.  In reversed round i a non-root v sends its partial result for the
+ * block it would have received, to its from-processor, and is then done with
+ * that block; it receives, from its to-processor, a partial result for the
+ * block it would have sent.  "Sent" marks take the place of possession marks:
+ * a block may be sent once only, and a partial result that arrives when the
+ * block has already been sent (this round's send included: send and receive
+ * are simultaneous) would be lost.  At the end every non-root must have sent
+ * all n blocks.  Verdict members: n_bad_recv_dup counts repeated sends,
+ * n_bad_send_unheld counts lost arrivals, the others as in orc_simulate;
+ * rounds are numbered as in the forward direction. */
+int orc_simulate_reduce(int64_t p, int64_t n, int64_t root, const int32_t *sched,
+                        orc_verdict *vd)
+{
+    int64_t skip[ORC_MAXQ + 2];
+    int q = orc_skips(p, skip);
+    if (q < 0 || n < 1 || root < 0 || root >= p || !vd) return -1;
+    skip[q + 1] = 0;
+    memset(vd, 0, sizeof *vd);
+    vd->first_bad = UINT64_MAX;
+    if (q == 0) return 0;
+    int32_t *vs = (int32_t *)malloc((size_t)p * 2 * q * sizeof(int32_t));
+    unsigned char *sent = (unsigned char *)calloc((size_t)p * (size_t)n, 1);
+    if (!vs || !sent) { free(vs); free(sent); return -2; }
+    for (int64_t v = 0; v < p; v++) {
+        int64_t r = (v + root) % p;
+        if (sched) {
+            memcpy(vs + v * 2 * q, sched + r * 2 * q, (size_t)2 * q * sizeof(int32_t));
+        } else {
+            recvschedule_sk(skip, q, p, v, vs + v * 2 * q, NULL);
+            sendschedule_sk(skip, q, p, v, vs + v * 2 * q + q, NULL, NULL);
+        }
+    }
+    int64_t x = (q - (n - 1) % q) % q;
+    for (int64_t i = (n + q - 1 + x) - 1; i >= x; i--) {
+        int k = (int)(i % q);
+        int64_t shift = -x + (int64_t)q * (i / q);
+        int64_t round = i - x;
+        /* first every send of this round, then every arrival */
+        for (int64_t v = 1; v < p; v++) {
+            int64_t r = (v + root) % p;
+            int64_t f = (v - skip[k] + p) % p;
+            int64_t rb = (int64_t)vs[v * 2 * q + k] + shift;       /* v sends this block to f */
+            int64_t sb = (int64_t)vs[f * 2 * q + q + k] + shift;   /* f expects this block   */
+            int has_r = rb >= 0, has_s = sb >= 0;
+            if (rb > n - 1) rb = n - 1;
+            if (sb > n - 1) sb = n - 1;
+            if (has_r != has_s || (has_r && rb != sb)) {
+                vd->n_edge_mismatch++;
+                vd->flags |= 1u << 2;
+                note_bad(vd, round, r);
+            }
+            if (has_r) {
+                if (sent[v * n + rb]) {
+                    vd->n_bad_recv_dup++;
+                    vd->flags |= 1u << 0;
+                    note_bad(vd, round, r);
+                } else {
+                    sent[v * n + rb] = 1;
+                }
+            }
+        }
+        for (int64_t v = 1; v < p; v++) {
+            int64_t r = (v + root) % p;
+            int64_t t = (v + skip[k]) % p;
+            if (t == 0) continue;                      /* the root sends nothing */
+            int64_t sb = (int64_t)vs[v * 2 * q + q + k] + shift;   /* arrives at v from t */
+            if (sb >= 0) {
+                if (sb > n - 1) sb = n - 1;
+                if (sent[v * n + sb]) {
+                    vd->n_bad_send_unheld++;
+                    vd->flags |= 1u << 1;
+                    note_bad(vd, round, r);
+                }
+            }
+        }
+        vd->rounds++;
+    }
+    for (int64_t v = 1; v < p; v++) {
+        int64_t have = 0;
+        for (int64_t j = 0; j < n; j++) have += sent[v * n + j];
+        if (have != n) {
+            vd->n_incomplete_ranks++;
+            vd->flags |= 1u << 3;
+            note_bad(vd, vd->rounds, (v + root) % p);
+        }
+    }
+    free(vs); free(sent);
+    return 0;
+}

@@ -144,6 +144,14 @@ int orc_edgecheck_table(int64_t p, const int32_t *sched, uint64_t *xor_recv, uin
 int orc_simulate(int64_t p, int64_t n, int64_t root, const int32_t *sched,
                  orc_verdict *verdict);
 
+/* Reduction to the root by running the rounds of Algorithm 1 backwards with
+ * all communication reversed (Section 2, observation on reduction), over "sent"
+ * marks.  n_bad_recv_dup counts sends of a block already sent, n_bad_send_unheld
+ * partial results that arrive after (or while) the block is sent on, the other
+ * members as in orc_simulate; rounds carry their forward numbers. */
+int orc_simulate_reduce(int64_t p, int64_t n, int64_t root, const int32_t *sched,
+                        orc_verdict *verdict);
+
 #ifdef __cplusplus
 }
 #endif

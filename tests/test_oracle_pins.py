@@ -539,3 +539,81 @@ def test_edgecheck_is_equal_exactly_when_conditions_1_and_2_hold():
     bad[[10, 500], q:] = good[[500, 10], q:]
     xr, xs = oracle.edgecheck_table(p, bad)
     assert xr != xs
+
+
+# ------------------------------------------------ reduction by reversal ----
+
+def reduce_with_payload(p, n, root, S):
+    """The rounds of Algorithm 1 backwards with real partial sums: in reversed
+    round i every non-root sends its partial result for recvblock[k] to its
+    from-processor and adds what arrives for sendblock[k] from its to-processor.
+    Asserts that nothing is sent twice or added to after it was sent, and that
+    the root ends with the sum of everybody's contribution for every block."""
+    sk = oracle.skips(p)
+    q = len(sk) - 1
+    init = lambda r, j: (r + 1) * 1000003 + (j + 7) * (r + 3)          # noqa: E731
+    part = [[init(r, j) for j in range(n)] for r in range(p)]
+    sent = [set() for _ in range(p)]
+    if q == 0:
+        return 0
+    x = (q - (n - 1) % q) % q
+    rounds = 0
+    for i in range((n + q - 1 + x) - 1, x - 1, -1):
+        k = i % q
+        shift = -x + q * (i // q)
+        inflight = {}
+        for r in range(p):
+            rb = int(S[r, k]) + shift
+            if r != root and rb >= 0:
+                rb = min(rb, n - 1)
+                assert rb not in sent[r], ("sends a block twice", p, n, r, i)
+                sent[r].add(rb)
+                inflight[(r - sk[k]) % p] = (rb, part[r][rb])
+        for r in range(p):
+            t = (r + sk[k]) % p
+            sb = int(S[r, q + k]) + shift
+            if sb >= 0 and t != root:
+                sb = min(sb, n - 1)
+                assert r in inflight, ("expects a partial result nobody sends", p, n, r, i)
+                blk, val = inflight.pop(r)
+                assert blk == sb
+                assert sb not in sent[r], ("partial result arrives after the block left", p, n, r, i)
+                part[r][sb] += val
+        assert not inflight
+        rounds += 1
+    for j in range(n):
+        assert part[root][j] == sum(init(r, j) for r in range(p))
+    for r in range(p):
+        if r != root:
+            assert sent[r] == set(range(n))
+    return rounds
+
+
+def test_reduction_by_reversal():
+    for p in list(range(1, 50)) + [100, 127, 128, 129, 257]:
+        q = oracle.q_of(p)
+        for root in {0, p // 3}:
+            S = oracle.schedules(p, root=root)
+            for n in {1, 2, max(q, 1), q + 1, 2 * q + 3}:
+                assert reduce_with_payload(p, n, root, S) == (n - 1 + q if q else 0)
+                assert_clean(oracle.simulate_reduce(p, n, root, S), p, n)
+    for p in range(1, 1200, 7):
+        q = oracle.q_of(p)
+        assert_clean(oracle.simulate_reduce(p, 2 * q + 3, p // 2), p, 2 * q + 3)
+    # planted mistakes show up
+    p, n = 100, 20
+    q = oracle.q_of(p)
+    good = oracle.schedules(p)
+    bad = good.copy()
+    bad[37, 2] = bad[37, 2] - 1 if bad[37, 2] > -q else bad[37, 2] + 1
+    vd = oracle.simulate_reduce(p, n, 0, bad)
+    assert vd["flags"] & 4 and vd["n_edge_mismatch"] > 0
+    bad = good.copy()
+    bad[10, 1] = bad[10, 0]
+    vd = oracle.simulate_reduce(p, n, 0, bad)
+    assert vd["flags"] & 1 and vd["flags"] & 8
+    bad = good.copy()
+    k = int(np.argmax(good[50, :q] >= 0))
+    bad[50, q + 0] = good[50, k]          # sent on before it can have arrived, seen backwards
+    vd = oracle.simulate_reduce(p, n, 0, bad)
+    assert vd["flags"] & 2 and vd["n_bad_send_unheld"] > 0

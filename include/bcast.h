@@ -159,6 +159,22 @@ int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roo
                    const int32_t *sched, void *workspace, size_t workspace_bytes,
                    bcast_verdict *verdict, void *stream);
 
+/* Reduction to the root over the same schedules (Section 2, the observation on
+ * reduction): the rounds of Algorithm 1 from the last one down to the first,
+ * with every communication reversed.  In reversed round i a non-root rank sends
+ * its partial result for the block it would have received to its
+ * from-processor and is then done with that block; it receives, from its
+ * to-processor, a partial result for the block it would have sent.  Bits mean
+ * "already sent on".  Checked: sender and receiver agree on the block; no block
+ * is sent twice (counted in n_bad_recv_dup, flag BCAST_V_RECV_DUP); no partial
+ * result arrives for a block that has been sent on, this round's send included
+ * (n_bad_send_unheld, BCAST_V_SEND_UNHELD); at the end every non-root has sent
+ * all n blocks (n_incomplete_ranks).  Rounds in first_bad carry their forward
+ * numbers.  Arguments, workspace and errors exactly as for bcast_simulate. */
+int bcast_simulate_reduce(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                          const int32_t *sched, void *workspace, size_t workspace_bytes,
+                          bcast_verdict *verdict, void *stream);
+
 /* Text for a return code; never NULL. */
 const char *bcast_strerror(int code);
 

@@ -78,6 +78,8 @@ def load_library():
     lib.bcast_simulate_workspace.restype = ctypes.c_size_t
     lib.bcast_simulate.argtypes = [u32, u32, ctypes.POINTER(u32), u32, vp, vp,
                                    ctypes.c_size_t, vp, vp]
+    lib.bcast_simulate_reduce.argtypes = lib.bcast_simulate.argtypes
+    lib.bcast_simulate_reduce.restype = ctypes.c_int
     lib.bcast_strerror.argtypes = [ctypes.c_int]
     lib.bcast_strerror.restype = ctypes.c_char_p
     for name in ("bcast_q", "bcast_skips", "bcast_schedules", "bcast_schedules_digest",
@@ -181,18 +183,24 @@ def bcast_simulate_workspace(p: int, n: int, n_roots: int) -> int:
     return int(load_library().bcast_simulate_workspace(p, n, n_roots))
 
 
-def bcast_simulate(p: int, n: int, roots, sched, workspace, verdict, stream=None) -> None:
+def bcast_simulate_reduce(p: int, n: int, roots, sched, workspace, verdict, stream=None) -> None:
+    """The reduction replay (rounds backwards); arguments as for bcast_simulate."""
+    bcast_simulate(p, n, roots, sched, workspace, verdict, stream, _entry="bcast_simulate_reduce")
+
+
+def bcast_simulate(p: int, n: int, roots, sched, workspace, verdict, stream=None,
+                   _entry: str = "bcast_simulate") -> None:
     """roots: sequence of ints (host); sched: device int32 [n_roots][p][2q] or None;
     workspace: device uint8 tensor; verdict: device uint8 tensor of
     n_roots * sizeof(bcast_verdict) bytes."""
     import torch
     roots = list(roots)
     arr = (ctypes.c_uint32 * max(len(roots), 1))(*roots)
-    _check(load_library().bcast_simulate(
+    _check(getattr(load_library(), _entry)(
         p, n, arr, len(roots), _dev_ptr(sched, torch.int32, "sched"),
         _dev_ptr(workspace, torch.uint8, "workspace"),
         0 if workspace is None else workspace.numel(),
-        _dev_ptr(verdict, torch.uint8, "verdict"), _stream_handle(stream)), "bcast_simulate")
+        _dev_ptr(verdict, torch.uint8, "verdict"), _stream_handle(stream)), _entry)
 
 
 def verdicts_from_bytes(raw: bytes) -> list[dict]:

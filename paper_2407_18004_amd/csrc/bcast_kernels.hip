@@ -325,6 +325,12 @@ __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rou
 // processors is schedule data, so the lane walks through all rounds by itself:
 // the sender-side check ("held before the round") reads the lane's own word
 // before this round's receive is marked.
+//
+// kReverse: the reduction to the root, i.e. the same rounds from the last one
+// down with all communication reversed.  The bits then mean "partial result
+// already sent on"; a lane first marks the block it sends (its receive entry),
+// then checks that what arrives (its send entry) is for a block it still has.
+template <bool kReverse>
 __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
   __shared__ int32_t st_recv[kSimMaxQ][kSimBlock];
   __shared__ int32_t st_send[kSimMaxQ][kSimBlock];
@@ -361,13 +367,16 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
 
     if (v != 0) {
       const int64_t nm1 = (int64_t)n - 1;
-      uint32_t k = prm.x % q;
-      int64_t shift = -(int64_t)prm.x + (int64_t)q * (prm.x / q);
+      // round i = x + round uses entry k = i mod q advanced by q * floor(i / q) - x
+      const uint32_t i0 = kReverse ? prm.x + prm.rounds - 1u : prm.x;
+      uint32_t k = i0 % q;
+      int64_t shift = -(int64_t)prm.x + (int64_t)q * (i0 / q);
       // The word of the possession column that was written last stays in a
       // register: blocks arrive in nearly increasing order, so a word serves
       // some 32 rounds before the next one is fetched.
       uint32_t cw = 0xFFFFFFFFu, cv = 0u;
-      for (uint32_t round = 0; round < prm.rounds; ++round) {
+      for (uint32_t step = 0; step < prm.rounds; ++step) {
+        const uint32_t round = kReverse ? prm.rounds - 1u - step : step;
         int64_t rb = (int64_t)st_recv[k][lane_b] + shift;
         int64_t fb = (int64_t)st_from[k][lane_b] + shift;
         int64_t sb = (int64_t)st_send[k][lane_b] + shift;
@@ -381,8 +390,9 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
         }
         const uint32_t sk = skip_at_level(pm1, q - k);
         const bool to_root = v + sk == p;
-        if (sb >= 0 && !to_root) {                  // state before this round
-          sb = sb > nm1 ? nm1 : sb;
+        const bool has_s = sb >= 0 && !to_root;
+        sb = sb > nm1 ? nm1 : sb;
+        if (!kReverse && has_s) {                   // state before this round
           const uint32_t w = (uint32_t)sb >> 5;
           const uint32_t word = w == cw ? cv : col[(uint64_t)w * p];
           if (((word >> ((uint32_t)sb & 31u)) & 1u) == 0) {
@@ -405,7 +415,19 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
             cv |= bit;
           }
         }
-        if (++k == q) { k = 0; shift += q; }
+        if (kReverse && has_s) {                    // state after this round's send
+          const uint32_t w = (uint32_t)sb >> 5;
+          const uint32_t word = w == cw ? cv : col[(uint64_t)w * p];
+          if (((word >> ((uint32_t)sb & 31u)) & 1u) != 0) {
+            ++n_unheld;
+            first_bad = key < first_bad ? key : first_bad;
+          }
+        }
+        if (kReverse) {
+          if (k == 0) { k = q - 1u; shift -= q; } else { --k; }
+        } else {
+          if (++k == q) { k = 0; shift += q; }
+        }
       }
       if (cw != 0xFFFFFFFFu) col[(uint64_t)cw * p] = cv;
       uint32_t have = 0;
@@ -620,9 +642,9 @@ size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots) {
   return bytes + 256;
 }
 
-int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
-                   const int32_t *sched, void *workspace, size_t workspace_bytes,
-                   bcast_verdict *verdict, void *stream) {
+static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *roots,
+                         uint32_t n_roots, const int32_t *sched, void *workspace,
+                         size_t workspace_bytes, bcast_verdict *verdict, void *stream) {
   const int q = host_q(p);
   if (q < 0 || n == 0 || n > (1u << 30) || n_roots == 0 || n_roots > 65535u || !roots || !verdict)
     return BCAST_EINVAL;
@@ -662,8 +684,23 @@ int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roo
   prm.roots = d_roots; prm.sched = sched; prm.table = table;
   prm.possession = possession; prm.verdict = verdict;
   dim3 grid((p + kSimBlock - 1) / kSimBlock, n_roots);
-  hipLaunchKernelGGL(k_simulate, grid, dim3(kSimBlock), 0, st, prm);
+  if (reverse) hipLaunchKernelGGL(k_simulate<true>, grid, dim3(kSimBlock), 0, st, prm);
+  else hipLaunchKernelGGL(k_simulate<false>, grid, dim3(kSimBlock), 0, st, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                   const int32_t *sched, void *workspace, size_t workspace_bytes,
+                   bcast_verdict *verdict, void *stream) {
+  return simulate_impl(false, p, n, roots, n_roots, sched, workspace, workspace_bytes, verdict,
+                       stream);
+}
+
+int bcast_simulate_reduce(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                          const int32_t *sched, void *workspace, size_t workspace_bytes,
+                          bcast_verdict *verdict, void *stream) {
+  return simulate_impl(true, p, n, roots, n_roots, sched, workspace, workspace_bytes, verdict,
+                       stream);
 }
 
 const char *bcast_strerror(int code) {

@@ -55,10 +55,10 @@ def gpu_edgecheck(p, root, a, b):
     return xr, xs
 
 
-def gpu_simulate(p, n, roots, sched=None):
+def gpu_simulate(p, n, roots, sched=None, reduce=False):
     ws = torch.empty(lib.bcast_simulate_workspace(p, n, len(roots)), dtype=torch.uint8, device=DEV)
     vd = torch.full((len(roots) * VERDICT_BYTES,), 0xAB, dtype=torch.uint8, device=DEV)
-    lib.bcast_simulate(p, n, roots, sched, ws, vd)
+    (lib.bcast_simulate_reduce if reduce else lib.bcast_simulate)(p, n, roots, sched, ws, vd)
     torch.cuda.synchronize()
     return verdicts_from_bytes(vd.cpu().numpy().tobytes())
 
@@ -374,3 +374,41 @@ def test_simulation_reports_planted_mistakes_like_the_oracle():
 def test_simulation_block_counts(p, n):
     root = p // 3
     assert gpu_simulate(p, n, [root])[0] == oracle.simulate(p, n, root)
+
+
+# ------------------------------------------------ reduction by reversal ----
+
+@pytest.mark.parametrize("p", [1, 2, 3, 17, 100, 1000, 4096, 65537])
+@pytest.mark.parametrize("n", [1, 2, 31, 64, 100])
+def test_reduction_replay_block_counts(p, n):
+    root = p // 3
+    got = gpu_simulate(p, n, [root], reduce=True)[0]
+    assert got == oracle.simulate_reduce(p, n, root)
+    assert got["flags"] == 0
+
+
+def test_reduction_replay_workload5_and_planted_mistakes():
+    p, n = workloads.SIMULATION_P, workloads.SIMULATION_N
+    roots = workloads.simulation_roots(64, seed=42)
+    got = gpu_simulate(p, n, roots, reduce=True)
+    for j, vd in enumerate(got):
+        assert vd["flags"] == 0 and vd["rounds"] == 272
+        if j % 32 == 0:
+            assert vd == oracle.simulate_reduce(p, n, roots[j])
+    p, n = 1000, 37
+    q = oracle.q_of(p)
+    roots = [0, 123, 999]
+    rng = np.random.default_rng(12)
+    tables = []
+    for root in roots:
+        tab = oracle.schedules(p, root=root)
+        for _ in range(5):
+            r, c = int(rng.integers(0, p)), int(rng.integers(0, 2 * q))
+            tab[r, c] = int(rng.integers(-q, q))
+        tables.append(tab)
+    tables[1][7, 2] = 10**9
+    sched = torch.from_numpy(np.stack(tables)).to(DEV)
+    got = gpu_simulate(p, n, roots, sched, reduce=True)
+    for j, root in enumerate(roots):
+        want = oracle.simulate_reduce(p, n, root, tables[j])
+        assert got[j] == want and want["flags"] != 0, (root, got[j], want)

@@ -12,8 +12,9 @@
  * q = ceil(log2 p) computed with integers (Section 2).
  *
  * What pins each function to something other than itself is listed next to
- * the tests; nothing here is "parity unpinned" except orc_digest's hash
- * (a definition of this build, not of the paper: only its flags are pinned).
+ * the tests; nothing here is "parity unpinned" except the hashes of orc_digest
+ * and orc_edgecheck (definitions of this build, not of the paper: the digest's
+ * flags and the edge check's equality are pinned, the hash values are not).
  */
 #ifndef BCAST_ORACLE_H
 #define BCAST_ORACLE_H

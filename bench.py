@@ -140,27 +140,29 @@ def run(args) -> dict:
 
 
 def bench_materialised(torch, lib, workloads, dev, args, counters) -> dict:
-    """The [p][2q] table of p = 1,000,003 (q = 20): 8q bytes written per rank."""
+    """The [p][2q] table of p = 1,000,003 (q = 20): 8q bytes written per rank; and, for the
+    rate the kernel reaches once a launch is long enough, 2^25 ranks of p = 2^31 - 1."""
     p = workloads.MATERIALISED_P
     q = lib.bcast_q(p)
     table = torch.empty((p, 2 * q), dtype=torch.int32, device=dev)
     reps = max(20, 4 * args.steps)
-    for _ in range(3):
-        lib.bcast_schedules(p, 0, 0, p, table, table, 2 * q, send_offset=q)
-    torch.cuda.synchronize()
-    evs = []
-    for _ in range(reps):
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        lib.bcast_schedules(p, 0, 0, p, table, table, 2 * q, send_offset=q)
-        e1.record()
-        evs.append((e0, e1))
-    torch.cuda.synchronize()
-    ms = sorted(a.elapsed_time(b) for a, b in evs)
-    med = ms[len(ms) // 2]
+    med = _median_ms(torch, lambda: lib.bcast_schedules(p, 0, 0, p, table, table, 2 * q,
+                                                        send_offset=q), reps)
     nbytes = 8.0 * q * p
+    del table
+    pl, nl = workloads.STREAMED_P, 1 << 25
+    ql = lib.bcast_q(pl)
+    big = torch.empty((nl, 2 * ql), dtype=torch.int32, device=dev)
+    med_l = _median_ms(torch, lambda: lib.bcast_schedules(pl, 0, 0, nl, big, big, 2 * ql,
+                                                          send_offset=ql), 5)
+    del big
+    large = {"workload": "ranks [0, 2^25) of p=2^31-1, int32 [2^25][62] table",
+             "median_launch_ms": med_l, "rank_schedules_per_s": nl / (med_l * 1e-3),
+             "hbm_write_GB_per_s": 8.0 * ql * nl / (med_l * 1e-3) / 1e9,
+             "frac_of_hbm_peak": 8.0 * ql * nl / (med_l * 1e-3) / PEAK_HBM,
+             "traffic": counters.get("k_schedules_long", {}).get("hbm_bytes_per_launch")}
     return {
+        "long_launch": large,
         "workload": "p=1000003 root=0 all ranks, int32 [p][40] table (bcast_schedules)",
         "kernel": "k_schedules", "median_launch_ms": med, "launches": reps,
         "rank_schedules_per_s": p / (med * 1e-3),

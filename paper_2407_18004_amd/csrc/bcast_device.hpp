@@ -354,26 +354,36 @@ __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint3
   return open;
 }
 
-// Phase three: the remaining violations of Algorithm 6, each by a receive
-// search for the to-processor that stops once entry k is out.
+// recvblock[k] of virtual rank t alone, by a receive search that stops once
+// entry k is out: what a violation of Algorithm 6 in round k asks for.
+__device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint32_t k,
+                                            uint32_t &flags) {
+  const uint32_t q = in.q;
+  const uint32_t jbt = baseblock_level(in.pm1, q, t);
+  int val = 0;
+  bool anomaly_t = false;
+  auto take = [&](uint32_t kk, int x) { if (kk == k) val = x; };
+  uint32_t got;
+  if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
+  else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
+  if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
+  return val;
+}
+
+// The to-processor of virtual rank v in round k.
+__device__ __forceinline__ uint32_t to_processor(const Instance &in, uint32_t v, uint32_t k) {
+  const uint32_t t = v + skip_at_level(in.pm1, in.q - k);
+  return t >= in.p ? t - in.p : t;
+}
+
+// Phase three: the remaining violations of Algorithm 6, each by its own search.
 __device__ __forceinline__ uint32_t resolve_by_search(const Instance &in, uint32_t v,
                                                       uint32_t viol, int8_t *send_row) {
-  const uint32_t q = in.q;
   uint32_t flags = 0;
   while (viol != 0) {
     const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
     viol &= viol - 1u;
-    uint32_t t = v + skip_at_level(in.pm1, q - k);
-    t = t >= in.p ? t - in.p : t;
-    const uint32_t jbt = baseblock_level(in.pm1, q, t);
-    int val = 0;
-    bool anomaly_t = false;
-    auto take = [&](uint32_t kk, int x) { if (kk == k) val = x; };
-    uint32_t got;
-    if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
-    else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
-    if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
-    send_row[k] = (int8_t)val;
+    send_row[k] = (int8_t)search_entry(in, to_processor(in, v, k), k, flags);
   }
   return flags;
 }

@@ -82,10 +82,17 @@ struct SchedParams {
   int layout;
 };
 
-// Wavefront w works through the tiles [w*run, (w+1)*run) from the highest
-// down, keeping the previous (= following in rank order) tile in the other
-// half of its LDS slice: a violation of Algorithm 6 asks for a row of a higher
-// rank, which is then usually still there.
+// How the tiles of a launch are dealt out.
+//  kShare = false: every wavefront works alone through its own run of tiles;
+//    only wavefront-level ordering of LDS is needed.  Used when Algorithm 6 has
+//    no violations to speak of.
+//  kShare = true: the four wavefronts of a workgroup take four consecutive tiles
+//    at a time ("unit").  A violation of Algorithm 6 asks for a row of a higher
+//    rank: the same tile or the next one, i.e. the slice of the wavefront next
+//    door, answers most of them.  What is left (targets far away or beyond the
+//    unit) goes into a queue in LDS and is worked off by as few lanes as there
+//    are entries, instead of by one nearly empty wavefront per tile.  All
+//    threads of a workgroup make the same number of calls (workgroup barriers).
 __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint64_t &t_hi) {
   const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
   const uint64_t run = (n_tiles + n_waves - 1) / n_waves;
@@ -94,66 +101,122 @@ __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint6
   t_hi = t_lo + run < n_tiles ? t_lo + run : n_tiles;
 }
 
-// LDS of the tiled kernels is sized at launch: per wavefront kNextTile + 1
-// slices of 64 rows of 2q bytes (rounded up to 16 bytes).
+// LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
+// rows of 2q bytes (rounded up to 16 bytes).
 __host__ __device__ inline uint32_t slice_words(uint32_t q) { return ((kWave * 2u * q + 15u) / 16u) * 4u; }
 
-template <bool kNextTile>
+constexpr uint32_t kQueueCap = 4u * kBlock;       // at most four violations per rank
+
+struct TileState {
+  uint32_t v, n_valid, flags;
+  int b;
+};
+
+// Computes the rows of tile `tile` (one per lane) into the wavefront's slice,
+// violations resolved.  slices: the workgroup's four slices, slice_w words each.
+template <bool kShare>
+__device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_begin,
+                                               uint64_t n_ranks, uint64_t tile, uint64_t n_tiles,
+                                               uint32_t *slices, uint32_t slice_w, uint32_t pitch,
+                                               uint32_t send_off, uint32_t lane, uint32_t wave) {
+  __shared__ uint2 queue[kShare ? kQueueCap : 1u];   // {to-processor, k | LDS byte offset << 8}
+  __shared__ uint32_t queue_n;
+  TileState st;
+  st.v = 0; st.flags = 0; st.b = 0;
+  int8_t *base = reinterpret_cast<int8_t *>(slices);
+  int8_t *tile_recv = reinterpret_cast<int8_t *>(slices + wave * slice_w);
+  int8_t *recv_row = tile_recv + lane * pitch;
+  int8_t *send_row = recv_row + send_off;
+  const uint64_t row0 = tile * kWave;
+  st.n_valid = tile < n_tiles ? (n_ranks - row0 < kWave ? (uint32_t)(n_ranks - row0) : kWave) : 0u;
+  uint32_t viol = 0;
+  if (lane < st.n_valid) {
+    st.v = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
+    viol = compute_rank_phase1(in, st.v, recv_row, send_row, st.b, st.flags);
+  }
+  if (kShare) {
+    if (threadIdx.x == 0) queue_n = 0;
+    __syncthreads();
+  } else {
+    wave_lds_sync();
+  }
+  if (lane < st.n_valid) {
+    const bool next_here = kShare && wave + 1u < kWavesPerBlock && tile + 1u < n_tiles;
+    const uint64_t left_next = next_here ? n_ranks - (row0 + kWave) : 0u;
+    const uint32_t n_valid_next = left_next < kWave ? (uint32_t)left_next : kWave;
+    const int8_t *next_recv =
+        next_here ? reinterpret_cast<const int8_t *>(slices + (wave + 1u) * slice_w) : nullptr;
+    uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, lane,
+                                       st.n_valid, n_valid_next);
+    if (kShare) {
+      while (open != 0) {
+        const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
+        open &= open - 1u;
+        const uint32_t slot = atomicAdd(&queue_n, 1u);
+        if (slot < kQueueCap)
+          queue[slot] = make_uint2(to_processor(in, st.v, k),
+                                   k | ((uint32_t)(send_row + k - base) << 8));
+        else                                   // cannot happen with at most four per rank
+          send_row[k] = (int8_t)search_entry(in, to_processor(in, st.v, k), k, st.flags);
+      }
+    } else {
+      st.flags |= resolve_by_search(in, st.v, open, send_row);
+    }
+  }
+  if (kShare) {
+    __syncthreads();
+    const uint32_t n_queued = queue_n < kQueueCap ? queue_n : kQueueCap;
+    for (uint32_t e = threadIdx.x; e < n_queued; e += kBlock) {
+      const uint2 item = queue[e];
+      base[item.y >> 8] = (int8_t)search_entry(in, item.x, item.y & 255u, st.flags);
+    }
+    __syncthreads();
+  } else {
+    wave_lds_sync();
+  }
+  return st;
+}
+
+template <bool kShare>
 __global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
-  constexpr uint32_t kBufs = kNextTile ? 2u : 1u;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
+  const uint32_t slice_w = slice_words(q);
   // row pitch, and offset of the send part inside the slice
   const uint32_t pitch = prm.layout == kSeparate ? q : 2u * q;
   const uint32_t send_off = prm.layout == kSeparate ? kWave * q : q;
+  uint32_t *words = lds_dyn + wave * slice_w;
+  const int8_t *recv_row = reinterpret_cast<const int8_t *>(words) + lane * pitch;
+  const int8_t *send_row = recv_row + send_off;
+  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
-  uint64_t t_lo, t_hi;
-  tile_run((prm.n_ranks + kWave - 1) / kWave, t_lo, t_hi);
-  uint32_t cur = 0, n_valid_next = 0;
-  const int8_t *next_recv = nullptr;
-  for (uint64_t tile = t_hi; tile-- > t_lo;) {
-    uint32_t *words = lds_dyn + (wave * kBufs + cur) * slice_words(q);
-    int8_t *tile_recv = reinterpret_cast<int8_t *>(words);
-    int8_t *recv_row = tile_recv + lane * pitch;
-    int8_t *send_row = recv_row + send_off;
+  auto one_tile = [&](uint64_t tile) {
+    const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
+                                           slice_w, pitch, send_off, lane, wave);
     const uint64_t row0 = tile * kWave;
-    const uint64_t left = prm.n_ranks - row0;
-    const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
-    uint32_t v = 0, viol = 0;
-    if (lane < n_valid) {
-      const uint32_t r = (uint32_t)(prm.r_begin + row0 + lane);
-      int b;
-      uint32_t fl;
-      v = virtual_rank(in, r);
-      viol = compute_rank_phase1(in, v, recv_row, send_row, b, fl);
-    }
-    wave_lds_sync();
-    if (lane < n_valid) {
-      viol = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, lane, n_valid,
-                                n_valid_next);
-      resolve_by_search(in, v, viol, send_row);
-    }
-    wave_lds_sync();
     if (prm.layout == kInterleaved) {
-      tile_out<false>(words, prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
+      tile_out<false>(words, prm.recv + row0 * 2u * q, st.n_valid * 2u * q, lane);
     } else if (prm.layout == kSeparate) {
-      tile_out<false>(words, prm.recv + row0 * q, n_valid * q, lane);
-      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
-    } else if (lane < n_valid) {
+      tile_out<false>(words, prm.recv + row0 * q, st.n_valid * q, lane);
+      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, st.n_valid * q, lane);
+    } else if (lane < st.n_valid) {
       int32_t *rr = prm.recv + (row0 + lane) * (uint64_t)prm.ld;
       int32_t *sr = prm.send + (row0 + lane) * (uint64_t)prm.ld;
       for (uint32_t k = 0; k < q; ++k) { rr[k] = recv_row[k]; sr[k] = send_row[k]; }
     }
-    if (kNextTile) {
-      next_recv = tile_recv;
-      n_valid_next = n_valid;
-      cur ^= 1u;
-    } else {
-      wave_lds_sync();                       // the one slice is rewritten next
-    }
+    if (!kShare) wave_lds_sync();            // the slice is rewritten next
+  };
+  if (kShare) {
+    const uint64_t n_units = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    for (uint64_t unit = blockIdx.x; unit < n_units; unit += gridDim.x)
+      one_tile(unit * kWavesPerBlock + wave);
+  } else {
+    uint64_t t_lo, t_hi;
+    tile_run(n_tiles, t_lo, t_hi);
+    for (uint64_t tile = t_lo; tile < t_hi; ++tile) one_tile(tile);
   }
 }
 
@@ -176,58 +239,45 @@ __global__ void k_edges_init(uint64_t *xors) {
 
 // kEdges = false: digest and flags.  kEdges = true: the two XOR sums of the
 // edge check go to prm.digest[0] and prm.digest[1]; flags are not touched.
-template <bool kNextTile, bool kEdges>
+template <bool kShare, bool kEdges>
 __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
-  constexpr uint32_t kBufs = kNextTile ? 2u : 1u;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
+  const uint32_t slice_w = slice_words(q);
+  const int8_t *row = reinterpret_cast<const int8_t *>(lds_dyn + wave * slice_w) + lane * 2u * q;
+  const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
   uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
-  uint64_t t_lo, t_hi;
-  tile_run((prm.n_ranks + kWave - 1) / kWave, t_lo, t_hi);
-  uint32_t cur = 0, n_valid_next = 0;
-  const int8_t *next_recv = nullptr;
-  for (uint64_t tile = t_hi; tile-- > t_lo;) {
-    int8_t *tile_recv = reinterpret_cast<int8_t *>(lds_dyn + (wave * kBufs + cur) * slice_words(q));
-    int8_t *recv_row = tile_recv + lane * 2u * q;
-    int8_t *send_row = recv_row + q;
-    const uint64_t row0 = tile * kWave;
-    const uint64_t left = prm.n_ranks - row0;
-    const uint32_t n_valid = left < kWave ? (uint32_t)left : kWave;
-    const bool valid = lane < n_valid;
-    const uint32_t r = (uint32_t)(prm.r_begin + row0 + lane);
-    uint32_t v = 0, viol = 0, fl = 0;
-    int b = 0;
-    if (valid) {
-      v = virtual_rank(in, r);
-      viol = compute_rank_phase1(in, v, recv_row, send_row, b, fl);
-    }
-    wave_lds_sync();
-    if (valid) {
-      viol = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, 2u * q, lane, n_valid,
-                                n_valid_next);
-      fl |= resolve_by_search(in, v, viol, send_row);
+  auto one_tile = [&](uint64_t tile) {
+    const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
+                                           slice_w, 2u * q, q, lane, wave);
+    acc_flags |= st.flags;
+    if (lane < st.n_valid) {
+      const uint32_t r = (uint32_t)(prm.r_begin + tile * kWave + lane);
       if (kEdges) {
-        edge_rank(in, r, recv_row, acc, acc2);
+        edge_rank(in, r, row, acc, acc2);
       } else {
         uint64_t h;
         uint32_t fl2;
-        digest_rank(in, r, v, b, recv_row, h, fl2);
+        digest_rank(in, r, st.v, st.b, row, h, fl2);
         acc ^= h;
-        acc_flags |= fl | fl2;
+        acc_flags |= fl2;
       }
     }
-    if (kNextTile) {
-      next_recv = tile_recv;
-      n_valid_next = n_valid;
-      cur ^= 1u;
-    } else {
-      wave_lds_sync();                       // the one slice is rewritten next
-    }
+    if (!kShare) wave_lds_sync();            // the slice is rewritten next
+  };
+  if (kShare) {
+    const uint64_t n_units = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    for (uint64_t unit = blockIdx.x; unit < n_units; unit += gridDim.x)
+      one_tile(unit * kWavesPerBlock + wave);
+  } else {
+    uint64_t t_lo, t_hi;
+    tile_run(n_tiles, t_lo, t_hi);
+    for (uint64_t tile = t_lo; tile < t_hi; ++tile) one_tile(tile);
   }
   acc = wave_xor64(acc);
   if (kEdges) acc2 = wave_xor64(acc2);
@@ -494,9 +544,10 @@ int persistent_grid(uint64_t n_blocks_wanted) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
-// Algorithm 6 has no violations when every skip below p is a power of two
-// (p = 2^q and p = 2^q - 1): no reason then to keep the following tile in LDS.
-// The choice only affects speed; an unexpected violation is resolved by search.
+// Algorithm 6 has (next to) no violations when every skip below p is a power of
+// two (p = 2^q and p = 2^q - 1): the wavefronts then work alone.  Otherwise the
+// workgroup shares rows and a queue (see tile_rows).  The choice only affects
+// speed: either way a violation that finds no row is resolved by search.
 bool keep_next_tile(uint32_t p) { return (p & (p - 1u)) != 0u && (p & (p + 1u)) != 0u; }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -551,7 +602,7 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
   const int grid = persistent_grid(blocks);
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
     hipLaunchKernelGGL(k_schedules<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
@@ -576,7 +627,7 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   const int grid = persistent_grid((n + kBlock - 1) / kBlock);
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
@@ -600,7 +651,7 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint6
   const int grid = persistent_grid((n + kBlock - 1) / kBlock);
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * 2u * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;

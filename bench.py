@@ -215,7 +215,21 @@ def bench_other(torch, lib, workloads, dev) -> dict:
                                                         ws, vd), 5)
     ms_64 = _median_ms(torch, lambda: lib.bcast_simulate(ps, n, roots, None, ws, vd), 5)
     rounds = n - 1 + q
+    # doubling (Observations 1 and 5): the table of 2p = 1,000,004 ranks from the one of 500,002
+    ph = 500_002
+    qh = lib.bcast_q(ph)
+    half = torch.empty((ph, 2 * qh), dtype=torch.int32, device=dev)
+    lib.bcast_schedules(ph, 0, 0, ph, half, half, 2 * qh, send_offset=qh)
+    full = torch.empty((2 * ph, 2 * (qh + 1)), dtype=torch.int32, device=dev)
+    ms_d = _median_ms(torch, lambda: lib.bcast_schedules_double(ph, half, full), 20)
+    bytes_d = 4.0 * half.numel() + 4.0 * full.numel()
     return {
+        "doubling": {"workload": "table of p=1,000,004 from the table of p=500,002 "
+                                 "(bcast_schedules_double)", "kernel": "k_double",
+                     "median_launch_ms": ms_d, "rank_schedules_per_s": 2 * ph / (ms_d * 1e-3),
+                     "roofline": {"bound": "hbm", "achieved": bytes_d / (ms_d * 1e-3) / 1e9,
+                                  "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                                  "frac": bytes_d / (ms_d * 1e-3) / PEAK_HBM}},
         "batched": {"workload": "8192 seeded instances x 4096 ranks (an eighth of workload 4)",
                     "kernel": "k_batched", "median_launch_ms": ms_b,
                     "rank_schedules_per_s": n_inst * m / (ms_b * 1e-3),

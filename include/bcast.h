@@ -122,6 +122,20 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin,
 int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin,
                               uint64_t r_end, uint64_t *xors, void *stream);
 
+/* Observations 1 and 5: the table for 2p processors from the table for p, both
+ * for root 0.  `in` is a device table int32 [p][2q] (row r = recv then send of
+ * rank r, as bcast_schedules writes it with ld = 2q), `out` a device table
+ * int32 [2p][2(q+1)]; they must not overlap.  Rank r < p and rank r + p are
+ * both derived from row r: negative entries drop by one, and a last round is
+ * added (receive: -1 for r < p, the new block q for r = p, the rank's
+ * non-negative block for r > p, which then leaves -1 behind; send: the rank's
+ * baseblock for r < p; for r >= p every non-negative entry and the new one
+ * are -1).  The result equals what bcast_schedules computes for 2p.  Pure
+ * data movement: 8q bytes read and 16(q+1) bytes written per given rank.
+ * Errors: p outside [1, (2^31-1)/2], NULL pointers (in may be NULL for p = 1),
+ * overlapping tables. */
+int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *stream);
+
 /* Many instances at once: instance i has p[i] processors, root[i], and asks for
  * the m physical ranks ranks[i*m .. i*m+m).  Row j of instance i, 2*q(p[i])
  * int32 {recv[0..q-1], send[0..q-1]}, is written at

@@ -73,6 +73,8 @@ def load_library():
     lib.bcast_schedules_digest.argtypes = [u32, u32, u64, u64, vp, vp, vp]
     lib.bcast_schedules_edgecheck.argtypes = [u32, u32, u64, u64, vp, vp]
     lib.bcast_schedules_edgecheck.restype = ctypes.c_int
+    lib.bcast_schedules_double.argtypes = [u32, vp, vp, vp]
+    lib.bcast_schedules_double.restype = ctypes.c_int
     lib.bcast_schedules_batched.argtypes = [u32, vp, vp, vp, u32, vp, vp, u64, vp, vp]
     lib.bcast_simulate_workspace.argtypes = [u32, u32, u32]
     lib.bcast_simulate_workspace.restype = ctypes.c_size_t
@@ -164,6 +166,15 @@ def bcast_schedules_edgecheck(p: int, root: int, r_begin: int, r_end: int, xors,
     _check(load_library().bcast_schedules_edgecheck(
         p, root, r_begin, r_end, _dev_ptr(xors, torch.int64, "xors"), _stream_handle(stream)),
         "bcast_schedules_edgecheck")
+
+
+def bcast_schedules_double(p: int, table_in, table_out, stream=None) -> None:
+    """table_in: device int32 [p][2q] for root 0 (None for p = 1); table_out: device int32
+    [2p][2(q+1)]."""
+    import torch
+    _check(load_library().bcast_schedules_double(
+        p, _dev_ptr(table_in, torch.int32, "table_in"), _dev_ptr(table_out, torch.int32, "table_out"),
+        _stream_handle(stream)), "bcast_schedules_double")
 
 
 def bcast_schedules_batched(n_inst: int, p, root, ranks, m: int, row_off, out,

@@ -289,6 +289,83 @@ __global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
   }
 }
 
+// ----------------------------------------------------------------- doubling
+
+struct DoubleParams {
+  uint32_t p, q;                 // the given instance; the result has 2p ranks and q + 1 rounds
+  const int32_t *in;             // [p][2q]
+  int32_t *out;                  // [2p][2(q+1)]
+};
+
+// Observations 1 and 5: the schedules for 2p processors from those for p
+// (root 0).  Rank r < p and rank r + p both start from row r: negative entries
+// drop by one (q grows by one), and a new last round is added.
+//   receive, r < p: the new entry is -1.  r = p: it is the new block q.
+//            r > p: the row's one non-negative block b moves to the new round
+//            and leaves -1 behind.
+//   send,    r < p: the new entry is the rank's baseblock (q for the root).
+//            r >= p: every non-negative entry becomes -1, so does the new one.
+// A wavefront reads 64 rows once (as bytes into LDS), each lane rewrites its
+// row twice, and both tiles leave as 16-byte stores: 8q bytes read and 16(q+1)
+// bytes written per given rank, nothing else.
+__global__ __launch_bounds__(kBlock) void k_double(DoubleParams prm) {
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t q = prm.q, q2 = q + 1u;
+  const uint32_t in_w = slice_words(q), out_w = slice_words(q2);
+  uint32_t *w_in = lds_dyn + wave * (in_w + 2u * out_w);
+  uint32_t *w_lo = w_in + in_w, *w_hi = w_lo + out_w;
+  const uint64_t n_tiles = ((uint64_t)prm.p + kWave - 1) / kWave;
+  for (uint64_t tile = (uint64_t)blockIdx.x * kWavesPerBlock + wave; tile < n_tiles;
+       tile += (uint64_t)gridDim.x * kWavesPerBlock) {
+    const uint64_t row0 = tile * kWave;
+    const uint32_t n_valid = prm.p - row0 < kWave ? (uint32_t)(prm.p - row0) : kWave;
+    // the tile is contiguous in memory: n_valid * 2q int32, four to a lane
+    const uint32_t n_in = n_valid * 2u * q;
+    const int32_t *src = prm.in + row0 * 2u * q;
+    int8_t *b_in = reinterpret_cast<int8_t *>(w_in);
+    if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+      const int4 *src4 = reinterpret_cast<const int4 *>(src);
+      for (uint32_t g = lane; g < (n_in >> 2); g += kWave) {
+        const int4 x = src4[g];
+        w_in[g] = ((uint32_t)x.x & 0xFFu) | (((uint32_t)x.y & 0xFFu) << 8) |
+                  (((uint32_t)x.z & 0xFFu) << 16) | ((uint32_t)x.w << 24);
+      }
+      for (uint32_t i = (n_in & ~3u) + lane; i < n_in; i += kWave) b_in[i] = (int8_t)src[i];
+    } else {
+      for (uint32_t i = lane; i < n_in; i += kWave) b_in[i] = (int8_t)src[i];
+    }
+    wave_lds_sync();
+    if (lane < n_valid) {
+      const int8_t *row = b_in + lane * 2u * q;
+      int8_t *lo = reinterpret_cast<int8_t *>(w_lo) + lane * 2u * q2;   // rank r
+      int8_t *hi = reinterpret_cast<int8_t *>(w_hi) + lane * 2u * q2;   // rank r + p
+      const bool is_root = row0 + lane == 0;
+      int b = (int)q;                                   // baseblock: the non-negative receive entry
+      for (uint32_t k = 0; k < q; ++k) {
+        const int rv = row[k];
+        b = rv >= 0 ? rv : b;
+        lo[k] = (int8_t)(rv < 0 ? rv - 1 : rv);
+        hi[k] = (int8_t)(rv < 0 ? rv - 1 : -1);
+      }
+      lo[q] = (int8_t)-1;
+      hi[q] = (int8_t)b;                                // the root's copy receives the new block q
+      for (uint32_t k = 0; k < q; ++k) {
+        const int sv = row[q + k];
+        lo[q2 + k] = (int8_t)(sv < 0 ? sv - 1 : sv);
+        hi[q2 + k] = (int8_t)(sv < 0 ? sv - 1 : -1);
+      }
+      lo[q2 + q] = (int8_t)(is_root ? (int)q : b);
+      hi[q2 + q] = (int8_t)-1;
+    }
+    wave_lds_sync();
+    tile_out<false>(w_lo, prm.out + row0 * 2u * q2, n_valid * 2u * q2, lane);
+    tile_out<false>(w_hi, prm.out + ((uint64_t)prm.p + row0) * 2u * q2, n_valid * 2u * q2, lane);
+    wave_lds_sync();
+  }
+}
+
 // ------------------------------------------------------------------ batched
 
 struct BatchParams {
@@ -657,6 +734,21 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint6
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || p > BCAST_MAX_P / 2u || !out || (q > 0 && !in)) return BCAST_EINVAL;
+  const uint64_t in_elems = (uint64_t)p * 2u * (uint32_t)q, out_elems = (uint64_t)p * 4u * ((uint32_t)q + 1u);
+  if (in && out + out_elems > in && in + in_elems > out) return BCAST_EINVAL;   // overlap
+  DoubleParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.in = in; prm.out = out;
+  const uint64_t tiles = ((uint64_t)p + kWave - 1) / kWave;
+  const int grid = persistent_grid((tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+  if (grid < 0) return BCAST_EHIP;
+  const size_t lds = (size_t)kWavesPerBlock * (slice_words(prm.q) + 2u * slice_words(prm.q + 1u)) * 4u;
+  hipLaunchKernelGGL(k_double, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 

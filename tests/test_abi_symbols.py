@@ -19,7 +19,7 @@ def built():
 def test_every_declared_symbol_is_exported(built):
     names = lib.exported_symbols()
     assert set(names) >= {"bcast_q", "bcast_skips", "bcast_schedules", "bcast_schedules_digest",
-                          "bcast_schedules_batched", "bcast_schedules_edgecheck", "bcast_simulate_workspace",
+                          "bcast_schedules_batched", "bcast_schedules_edgecheck", "bcast_schedules_double", "bcast_simulate_workspace",
                           "bcast_simulate", "bcast_simulate_reduce", "bcast_strerror"}
     for name in names:
         assert isinstance(getattr(built, name), ctypes._CFuncPtr), name

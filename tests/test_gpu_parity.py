@@ -412,3 +412,34 @@ def test_reduction_replay_workload5_and_planted_mistakes():
     for j, root in enumerate(roots):
         want = oracle.simulate_reduce(p, n, root, tables[j])
         assert got[j] == want and want["flags"] != 0, (root, got[j], want)
+
+
+# ------------------------------------------------- doubling (even p) -------
+
+@pytest.mark.parametrize("p", [1, 2, 3, 9, 17, 64, 100, 1000, 4097, 65537, 500002, 2**20 - 1])
+def test_doubling_equals_the_schedules_of_2p(p):
+    # Observations 1 and 5 on the GPU: table(2p) from table(p), against the oracle's table(2p)
+    q = lib.bcast_q(p)
+    src = torch.from_numpy(oracle.schedules(p)).to(DEV) if q else None
+    dst = torch.full((2 * p, 2 * (q + 1)), 55, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules_double(p, src, dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), oracle.schedules(2 * p))
+
+
+def test_doubling_chain_from_the_gpu_table_and_errors():
+    # 125,001 -> 250,002 -> 500,004 -> 1,000,008 from a table computed on the GPU
+    p = 125001
+    cur = torch.from_numpy(gpu_table(p)).to(DEV)
+    for _ in range(3):
+        q = lib.bcast_q(p)
+        nxt = torch.empty((2 * p, 2 * (q + 1)), dtype=torch.int32, device=DEV)
+        lib.bcast_schedules_double(p, cur, nxt)
+        p, cur = 2 * p, nxt
+    torch.cuda.synchronize()
+    assert p == 1000008
+    assert np.array_equal(cur.cpu().numpy(), oracle.schedules(p))
+    with pytest.raises(lib.BcastError):
+        lib.bcast_schedules_double(2**30, cur, cur)
+    with pytest.raises(lib.BcastError):
+        lib.bcast_schedules_double(1000008, cur, cur)          # overlap

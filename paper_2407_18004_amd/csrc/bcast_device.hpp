@@ -410,33 +410,46 @@ __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint
   const uint32_t two_q = 2u * q;
   const bool is_root = v == 0;
   uint64_t seen = 0;
-  uint32_t bad_range = 0, bad_c4 = 0, bad_s0 = 0;
-  const uint64_t always = is_root ? 0ull : 1ull << b;          // b - q may always be sent
+  uint32_t u_max = 0, bad_c4 = 0;
+  const uint64_t always = is_root ? ~0ull : 1ull << b;         // b - q may always be sent
   for (uint32_t k = 0; k < q; ++k) {
-    const uint32_t ur = (uint32_t)((int)row[k] + (int)q);
+    const uint32_t ur = (uint32_t)((int)row[k] + (int)q);        // value + q: in range iff < 2q
     const uint32_t us = (uint32_t)((int)row[q + k] + (int)q);
-    bad_range |= (uint32_t)(ur >= two_q) | (uint32_t)(us >= two_q);
+    u_max = ur > u_max ? ur : u_max;
+    u_max = us > u_max ? us : u_max;
     const uint64_t allowed = seen | always;
-    bad_c4 |= (uint32_t)(((allowed >> (us & 63u)) & 1ull) == 0ull && k != 0);
-    bad_s0 |= (uint32_t)(is_root ? us != q + k : (k == 0 && us != (uint32_t)b));
+    bad_c4 |= (uint32_t)(((allowed >> (us & 63u)) & 1ull) == 0ull && k != 0);  // round 0: send0
     seen |= 1ull << (ur & 63u);
   }
+  // sendblock[0] is b - q by Condition 4 (value + q = b); the root sends block k in round k
+  bool bad_s0 = !is_root && q > 0 && (uint32_t)((int)row[q] + (int)q) != (uint32_t)b;
+  if (__any(is_root)) {
+    if (is_root)
+      for (uint32_t k = 0; k < q; ++k) bad_s0 = bad_s0 || (int)row[q + k] != (int)k;
+  }
+  const bool bad_range = u_max >= two_q && q > 0;
   const uint64_t low = q >= 32 ? 0xFFFFFFFFull : ((1ull << q) - 1ull);
   const uint64_t want = is_root ? low : ((low ^ (1ull << b)) | (1ull << (q + (uint32_t)b)));
-  flags = (seen == want && bad_range == 0 ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
-          ((bad_c4 && !is_root) ? BCAST_F_COND4 : 0u) | (bad_range ? BCAST_F_RANGE : 0u);
+  flags = (seen == want && !bad_range ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
+          (bad_c4 ? BCAST_F_COND4 : 0u) | (bad_range ? BCAST_F_RANGE : 0u);
 
+  // ten six-bit fields per word; full words first, then the tail
   uint64_t h = sm64(((uint64_t)in.p << 32) ^ (uint64_t)r);
-  for (uint32_t f0 = 0; f0 < two_q; f0 += 10) {
-    uint32_t lo = 0, hi = 0;                                     // fields 0-4 and 5-9 of the word
+  uint32_t f0 = 0;
+  for (; f0 + 10u <= two_q; f0 += 10u) {
+    uint32_t lo = 0, hi = 0;
 #pragma unroll
     for (uint32_t t = 0; t < 5; ++t) {
-      const uint32_t fa = f0 + t < two_q ? ((uint32_t)(int)row[f0 + t] + 32u) & 63u : 0u;
-      const uint32_t fb = f0 + 5 + t < two_q ? ((uint32_t)(int)row[f0 + 5 + t] + 32u) & 63u : 0u;
-      lo |= fa << (6u * t);
-      hi |= fb << (6u * t);
+      lo |= (((uint32_t)(int)row[f0 + t] + 32u) & 63u) << (6u * t);
+      hi |= (((uint32_t)(int)row[f0 + 5u + t] + 32u) & 63u) << (6u * t);
     }
     h = sm64(h ^ ((uint64_t)lo | ((uint64_t)hi << 30)));
+  }
+  if (f0 < two_q) {
+    uint64_t w = 0;
+    for (uint32_t t = 0; f0 + t < two_q; ++t)
+      w |= (uint64_t)(((uint32_t)(int)row[f0 + t] + 32u) & 63u) << (6u * t);
+    h = sm64(h ^ w);
   }
   hash = h;
 }

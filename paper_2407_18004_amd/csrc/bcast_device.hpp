@@ -334,13 +334,13 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
 // the same tile, or in the following tile of 64 ranks whose rows are still in
 // LDS, its row is read instead of recomputed.  tile_recv and next_recv point at
 // the receive row of lane 0 of the two tiles (next_recv may be null); rows are
-// row_pitch bytes apart.  Returns the violations that are still open.  Call
-// after phase one of the tile is complete and visible.
+// row_pitch and next_pitch bytes apart.  Returns the violations that are still
+// open.  Call after phase one of the tile is complete and visible.
 __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint32_t viol,
                                                        int8_t *send_row, const int8_t *tile_recv,
                                                        const int8_t *next_recv, uint32_t row_pitch,
-                                                       uint32_t lane, uint32_t n_valid,
-                                                       uint32_t n_valid_next) {
+                                                       uint32_t next_pitch, uint32_t lane,
+                                                       uint32_t n_valid, uint32_t n_valid_next) {
   uint32_t open = 0;
   while (viol != 0) {
     const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
@@ -348,7 +348,7 @@ __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint3
     const uint32_t tl = lane + skip_at_level(in.pm1, in.q - k);   // < 2^32: lane < 64, skip < 2^31
     if (tl < n_valid) send_row[k] = tile_recv[tl * row_pitch + k];
     else if (next_recv != nullptr && n_valid == 64u && tl - 64u < n_valid_next)
-      send_row[k] = next_recv[(tl - 64u) * row_pitch + k];
+      send_row[k] = next_recv[(tl - 64u) * next_pitch + k];
     else open |= 1u << k;
   }
   return open;

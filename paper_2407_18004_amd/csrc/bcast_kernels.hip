@@ -94,11 +94,11 @@ struct SchedParams {
 //    are entries, instead of by one nearly empty wavefront per tile.  All
 //    threads of a workgroup make the same number of calls (workgroup barriers).
 __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint64_t &t_hi) {
+  // wavefront w of W takes tiles [w n / W, (w + 1) n / W): runs differ by one tile at most
   const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-  const uint64_t run = (n_tiles + n_waves - 1) / n_waves;
   const uint64_t w = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  t_lo = w * run < n_tiles ? w * run : n_tiles;
-  t_hi = t_lo + run < n_tiles ? t_lo + run : n_tiles;
+  t_lo = w * n_tiles / n_waves;                 // n_tiles <= 2^25, W < 2^32: no overflow
+  t_hi = (w + 1u) * n_tiles / n_waves;
 }
 
 // LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
@@ -146,8 +146,8 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
     const uint32_t n_valid_next = left_next < kWave ? (uint32_t)left_next : kWave;
     const int8_t *next_recv =
         next_here ? reinterpret_cast<const int8_t *>(slices + (wave + 1u) * slice_w) : nullptr;
-    uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, lane,
-                                       st.n_valid, n_valid_next);
+    uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, pitch,
+                                       lane, st.n_valid, n_valid_next);
     if (kShare) {
       while (open != 0) {
         const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
@@ -177,8 +177,39 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
   return st;
 }
 
+// Deferred violations of k_schedules<true>.  A wavefront works through its run
+// of tiles from the highest down and keeps the receive rows of the tile it has
+// just finished (64 rows of q bytes), so a violation of Algorithm 6 whose
+// to-processor is at most one tile up is answered from LDS.  The others are not
+// searched for on the spot, where they would occupy a few lanes of an otherwise
+// idle wavefront per tile: the row leaves with the entry still open, {row, k}
+// goes into a queue in LDS, and whenever 64 are waiting, and once more at the
+// end of the run, one search per lane fills them in and stores the entries
+// straight into the table.
+constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefront
+
+// words of LDS per wavefront: slice, receive rows of the tile above, queue
+__host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
+  return slice_words(q) + 16u * q + 2u * kDeferCap;
+}
+
+__device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
+                                               const uint2 *queue, uint32_t lo, uint32_t hi,
+                                               uint32_t lane) {
+  // The rows were stored by this wavefront; they must have landed before single
+  // entries of them are overwritten.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (lo + lane < hi) {
+    const uint2 item = queue[lo + lane];             // {row in the launch, k}
+    const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + item.x));
+    uint32_t fl = 0;
+    prm.send[(uint64_t)item.x * (uint64_t)prm.ld + item.y] =
+        search_entry(in, to_processor(in, v, item.y), item.y, fl);
+  }
+}
+
 template <bool kShare>
-__global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_schedules(SchedParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
@@ -188,36 +219,80 @@ __global__ __launch_bounds__(kBlock) void k_schedules(SchedParams prm) {
   // row pitch, and offset of the send part inside the slice
   const uint32_t pitch = prm.layout == kSeparate ? q : 2u * q;
   const uint32_t send_off = prm.layout == kSeparate ? kWave * q : q;
-  uint32_t *words = lds_dyn + wave * slice_w;
-  const int8_t *recv_row = reinterpret_cast<const int8_t *>(words) + lane * pitch;
-  const int8_t *send_row = recv_row + send_off;
+  uint32_t *words = lds_dyn + wave * (kShare ? deferred_wave_words(q) : slice_w);
+  int8_t *tile_recv = reinterpret_cast<int8_t *>(words);
+  int8_t *recv_row = tile_recv + lane * pitch;
+  int8_t *send_row = recv_row + send_off;
   const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
-  auto one_tile = [&](uint64_t tile) {
-    const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                           slice_w, pitch, send_off, lane, wave);
-    const uint64_t row0 = tile * kWave;
+  auto copy_out = [&](uint64_t row0, uint32_t n_valid) {
     if (prm.layout == kInterleaved) {
-      tile_out<false>(words, prm.recv + row0 * 2u * q, st.n_valid * 2u * q, lane);
+      tile_out<false>(words, prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
     } else if (prm.layout == kSeparate) {
-      tile_out<false>(words, prm.recv + row0 * q, st.n_valid * q, lane);
-      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, st.n_valid * q, lane);
-    } else if (lane < st.n_valid) {
+      tile_out<false>(words, prm.recv + row0 * q, n_valid * q, lane);
+      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
+    } else if (lane < n_valid) {
       int32_t *rr = prm.recv + (row0 + lane) * (uint64_t)prm.ld;
       int32_t *sr = prm.send + (row0 + lane) * (uint64_t)prm.ld;
       for (uint32_t k = 0; k < q; ++k) { rr[k] = recv_row[k]; sr[k] = send_row[k]; }
     }
-    if (!kShare) wave_lds_sync();            // the slice is rewritten next
   };
-  if (kShare) {
-    const uint64_t n_units = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    for (uint64_t unit = blockIdx.x; unit < n_units; unit += gridDim.x)
-      one_tile(unit * kWavesPerBlock + wave);
-  } else {
-    uint64_t t_lo, t_hi;
-    tile_run(n_tiles, t_lo, t_hi);
-    for (uint64_t tile = t_lo; tile < t_hi; ++tile) one_tile(tile);
+
+  uint64_t t_lo, t_hi;
+  tile_run(n_tiles, t_lo, t_hi);
+  if (!kShare) {
+    for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
+      const TileState st = tile_rows<false>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
+                                            slice_w, pitch, send_off, lane, wave);
+      copy_out(tile * kWave, st.n_valid);
+      wave_lds_sync();                         // the slice is rewritten next
+    }
+    return;
   }
+
+  int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
+  uint2 *queue = reinterpret_cast<uint2 *>(words + slice_w + 16u * q);
+  uint32_t n_queued = 0;                       // the same in all lanes
+  uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
+  for (uint64_t tile = t_hi; tile-- > t_lo;) {
+    const uint64_t row0 = tile * kWave;
+    const uint32_t n_valid = prm.n_ranks - row0 < kWave ? (uint32_t)(prm.n_ranks - row0) : kWave;
+    uint32_t v = 0, viol = 0, flags = 0;
+    int b = 0;
+    if (lane < n_valid) {
+      v = virtual_rank(in, (uint32_t)(prm.r_begin + row0 + lane));
+      viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags);
+    }
+    wave_lds_sync();
+    uint32_t open = 0;
+    if (lane < n_valid)
+      open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
+                                pitch, q, lane, n_valid, n_valid_above);
+    while (__any(open != 0)) {
+      const bool has = open != 0;
+      const uint64_t who = __ballot(has);
+      const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
+      if (has) {
+        const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
+        open &= open - 1u;
+        if (slot < kDeferCap) queue[slot] = make_uint2((uint32_t)(row0 + lane), k);
+        else send_row[k] = (int8_t)search_entry(in, to_processor(in, v, k), k, flags);
+      }
+      const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
+      n_queued = n_new < kDeferCap ? n_new : kDeferCap;
+    }
+    wave_lds_sync();
+    copy_out(row0, n_valid);
+    if (lane < n_valid)
+      for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+    n_valid_above = n_valid;
+    while (n_queued >= (uint32_t)kWave) {
+      deferred_flush(in, prm, queue, n_queued - kWave, n_queued, lane);
+      n_queued -= kWave;
+    }
+    wave_lds_sync();                           // slice and queue are rewritten next
+  }
+  deferred_flush(in, prm, queue, 0u, n_queued, lane);
 }
 
 // ------------------------------------------------------------------- digest
@@ -240,7 +315,7 @@ __global__ void k_edges_init(uint64_t *xors) {
 // kEdges = false: digest and flags.  kEdges = true: the two XOR sums of the
 // edge check go to prm.digest[0] and prm.digest[1]; flags are not touched.
 template <bool kShare, bool kEdges>
-__global__ __launch_bounds__(kBlock) void k_digest(DigestParams prm) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
@@ -381,7 +456,7 @@ __global__ void k_u32_zero(uint32_t *x) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *x = 0;
 }
 
-__global__ __launch_bounds__(kBlock) void k_batched(BatchParams prm) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
   __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = threadIdx.x / kWave;
@@ -621,6 +696,28 @@ int persistent_grid(uint64_t n_blocks_wanted) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// Grid of k_schedules<true>, whose wavefronts each take one contiguous run of
+// tiles.  Long runs make the deferred violations cheap; many more workgroups
+// than fit at once even out the load, because a SIMD serves its oldest
+// wavefront first and the young ones of a resident set fall behind by a factor
+// of two.  Measured on MI355X: about six tiles per wavefront is best for long
+// tables, two to four when that would leave fewer than two resident sets.
+constexpr uint64_t kRunTiles = 6;
+int run_grid(uint64_t n_tiles) {
+  const int cap = persistent_grid(UINT64_MAX);                  // 64 workgroups per CU
+  if (cap < 0) return -1;
+  const uint64_t one_set = (uint64_t)(cap / 64) * 8u;            // 8 workgroups per CU fit at once
+  const uint64_t per_wg = kWavesPerBlock;
+  const uint64_t g_one = (n_tiles + per_wg - 1) / per_wg;        // one tile per wavefront
+  if (g_one <= one_set) return (int)(g_one == 0 ? 1 : g_one);
+  const uint64_t g_two = (n_tiles + per_wg * 2u - 1) / (per_wg * 2u);
+  const uint64_t floor_g = g_two < 2u * one_set ? g_two : 2u * one_set;
+  uint64_t g = (n_tiles + per_wg * kRunTiles - 1) / (per_wg * kRunTiles);
+  if (g < floor_g) g = floor_g;
+  if (g > (uint64_t)cap) g = (uint64_t)cap;
+  return (int)g;
+}
+
 // Algorithm 6 has (next to) no violations when every skip below p is a power of
 // two (p = 2^q and p = 2^q - 1): the wavefronts then work alone.  Otherwise the
 // workgroup shares rows and a queue (see tile_rows).  The choice only affects
@@ -676,12 +773,14 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
     prm.layout = kRowwise;
   }
   const uint64_t blocks = (n + kBlock - 1) / kBlock;
-  const int grid = persistent_grid(blocks);
-  if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
+    const int grid = run_grid((n + kWave - 1) / kWave);
+    if (grid < 0) return BCAST_EHIP;
     hipLaunchKernelGGL(k_schedules<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
+    const int grid = persistent_grid(blocks);
+    if (grid < 0) return BCAST_EHIP;
     const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
     hipLaunchKernelGGL(k_schedules<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }

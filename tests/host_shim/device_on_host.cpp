@@ -68,7 +68,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
       int8_t *recv_row = tile + lane * 2 * q;
       const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
-                                               2 * q, lane, n_valid, n_valid_next);
+                                               2 * q, 2 * q, lane, n_valid, n_valid_next);
       borrowed += (uint64_t)__popc(viol[lane] ^ open);
       fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
     }

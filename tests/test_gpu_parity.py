@@ -146,6 +146,40 @@ def test_output_layouts_agree():
     assert np.array_equal(flat.cpu().numpy()[1:].reshape(n, 2 * q), want)
 
 
+@pytest.mark.parametrize("p,root,a,b", [
+    (4000037, 123457, 1000, 2200000),     # few violations per rank, long runs of tiles
+    (2097153, 0, 0, 2097153),             # p = 2^21 + 1: more than one violation per rank
+    (2097153, 2097152, 5, 2097100),
+])
+def test_long_runs_with_deferred_violations(p, root, a, b):
+    # Tables long enough that a wavefront works through several tiles and fills
+    # in the violations of Algorithm 6 later, in batches, in all three layouts.
+    q = lib.bcast_q(p)
+    n = b - a
+    want = oracle.schedules(p, root=root, r_begin=a, r_end=b, send_mode=1)
+    t = torch.full((n, 2 * q), 99, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules(p, root, a, b, t, t, 2 * q, send_offset=q)
+    torch.cuda.synchronize()
+    assert np.array_equal(t.cpu().numpy(), want)
+    del t
+    recv = torch.full((n, q), 99, dtype=torch.int32, device=DEV)
+    send = torch.full((n, q), 99, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules(p, root, a, b, recv, send, q)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy(), want[:, :q])
+    assert np.array_equal(send.cpu().numpy(), want[:, q:])
+    del recv, send
+    ld = 2 * q + 3
+    tab = torch.full((n, ld), 1234, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules(p, root, a, b, tab, tab, ld, send_offset=q)
+    torch.cuda.synchronize()
+    got = tab.cpu().numpy()
+    assert np.array_equal(got[:, :2 * q], want) and (got[:, 2 * q:] == 1234).all()
+    # send by definition on a seeded sample
+    ranks = np.sort(workloads.streamed_sample_ranks(512, seed=11, p=n).astype(np.int64)) + a
+    assert np.array_equal(want[ranks - a], oracle.schedules_ranks(p, root, ranks.astype(np.uint32), send_mode=0))
+
+
 def test_argument_errors():
     t = torch.zeros((16, 40), dtype=torch.int32, device=DEV)
     with pytest.raises(lib.BcastError) as e:

@@ -187,6 +187,55 @@ __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r)
   return r >= in.root ? r - in.root : r + (in.p - in.root);
 }
 
+// Cross-lane helpers for values that must be the same in all lanes.
+__device__ __forceinline__ uint32_t lane0_of(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+}
+__device__ __forceinline__ uint32_t wave_min32(uint32_t x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t y = (uint32_t)__shfl_xor((int)x, m, 64);
+    x = y < x ? y : x;
+  }
+  return x;
+}
+__device__ __forceinline__ uint32_t wave_max32(uint32_t x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    const uint32_t y = (uint32_t)__shfl_xor((int)x, m, 64);
+    x = y > x ? y : x;
+  }
+  return x;
+}
+
+// What a wavefront remembers of the lockstep stretch of one tile, to replay it
+// on later tiles of its run (see recv_search_fast).  `levels` points at 32 bytes
+// of the wavefront's own LDS; everything except D and M is the same in all lanes.
+struct LockstepCache {
+  uint8_t *levels;                  // level accepted for round k, k = k_entry .. q-1
+  uint32_t valid;
+  uint32_t k, live, pathr, j;       // state on entry to the stretch
+  uint32_t D, M;                    // this lane's D and M on entry
+  uint32_t margin;                  // how far D and M may move before a test flips
+  uint32_t iters;                   // iterations the stretch took
+  uint32_t replays;                 // tiles that took the record (statistics)
+};
+
+__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint8_t *levels) {
+  c.levels = levels;
+  c.valid = 0; c.k = 0; c.live = 0; c.pathr = 0; c.j = 0; c.D = 0; c.M = 0; c.margin = 0; c.iters = 0; c.replays = 0;
+}
+
+struct TrackOff { static constexpr bool value = false; };
+struct TrackOn { static constexpr bool value = true; };
+
+// How far the difference x - y of a test "x >= y" is from flipping: the test
+// keeps its outcome as long as the difference moves by no more than this.
+__device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
+  const int dxy = (int)(x - y);                 // all operands are below 2^31
+  return (uint32_t)(dxy ^ (dxy >> 31));           // d for d >= 0, -1 - d for d < 0
+}
+
 // The receive search again, in the form the kernels use: same state and same
 // tests as recv_search, reorganised around how the search actually runs.
 //
@@ -204,10 +253,25 @@ __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r)
 // call, so the walk starts below it with D = v and level 0 on the path; for
 // the root level 0 is not in the list and the walk starts with D = p.  v = 1
 // (level 0 accepted directly, D = p + 1) is left to recv_search by the caller.
+//
+// 3. Replay.  Once the lanes are in lockstep, the rest of the search is a
+//    function of (k, live, path, cursor), which all lanes share, and of each
+//    lane's D and M, which enter only through tests of the form x >= y where x
+//    and y are D + c, M + c or constants.  The next tiles of a wavefront's run
+//    usually arrive with the same shared state and with D and M moved by the
+//    same small amount in every lane.  So a wavefront that runs the stretch
+//    also records, per test, how far it was from flipping; a later tile whose
+//    D and M differ from the recorded ones by less than the smallest such
+//    distance makes the same moves, and takes the recorded accepts (level per
+//    round) instead of running the loop.  The same bound, applied to the
+//    differences between the lanes of the recording tile, shows that its lanes
+//    did make the same moves.  `use_cache` = false: no replay; when it is true,
+//    all lanes of the wavefront must be in the call.
 template <typename Emit>
 __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, uint32_t q,
                                                      uint32_t v, uint32_t jb, uint32_t k_last,
-                                                     bool &anomaly, Emit emit) {
+                                                     bool &anomaly, Emit emit,
+                                                     LockstepCache &cache, bool use_cache) {
   const bool is_root = v == 0;
   const int b = (int)q - (int)jb;
   // Descent.  W = D - 2 as a signed number; after the accept W = -1, which
@@ -262,8 +326,14 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
   }
   bool go = k < k_stop && !((int)j < 0 && pathr == 0);
   uint32_t it = 0;
-  for (uint32_t phase = 0; phase < 2u; ++phase)
-  for (; it < cap && go && (phase == 1u || (live & deep) != 0u); ++it) {
+  uint32_t margin = 0xFFFFFFFFu;
+  // One move of the state machine.  With kTrack, every test that decides the
+  // move also lowers `margin` to its flip distance.
+  auto move = [&](auto track_tag) {
+    constexpr bool kTrack = decltype(track_tag)::value;
+    auto see = [&](uint32_t x, uint32_t y) {
+      if (kTrack) { const uint32_t fd = flip_distance(x, y); margin = fd < margin ? fd : margin; }
+    };
     uint32_t jj, a, t;
     bool post;
     if ((int)j < 0) {                       // list exhausted: back to the pending call
@@ -277,10 +347,16 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
       jj = j;
       a = skip_at_level(pm1, jj);
       t = D - a;
-      const bool pass = a <= D && t >= M;
+      see(D, a);
+      const bool fits = a <= D;
+      if (kTrack && fits) see(t, M);
+      const bool pass = fits && t >= M;
+      if (kTrack && pass) see(t, sk1);
       const bool rec = pass && t >= sk1;
       post = pass && !rec;
       if (rec) {                            // recursive call on r' + skip[e]
+        see(t, a);
+        if (kTrack && a <= t) see(t - a, M);
         anom |= (uint32_t)(a <= t && t - a >= M);
         D = t;
         pathr |= 0x80000000u >> jj;
@@ -288,9 +364,12 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
     }
     bool ret = false;
     if (post) {
+      see(D, sk1);
       if (D >= sk1) {                       // accept e for round k
         emit(k, jj == 0 ? b : -(int)jj);
+        if (kTrack) cache.levels[k] = (uint8_t)jj;
         live ^= 1u << jj;
+        see(sk1, t + 2u);
         M = sk1 > t + 1u ? sk1 : t + 1u;
         ++k;
         sk1 = skip_at_level(pm1, (q - k - 1u) & 31u);     // skip[k+1]; unused once k = q
@@ -300,6 +379,50 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
     }
     j = ret ? kEndLevel : next_level(live, jj);
     go = k < k_stop && !((int)j < 0 && pathr == 0);
+  };
+  for (; it < cap && go && (live & deep) != 0u; ++it) move(TrackOff{});
+  // Lockstep stretch: replayed, recorded, or simply run.
+  bool replayed = false, record = false;
+  uint32_t D_in = D, M_in = M, k_in = k, live_in = live, pathr_in = pathr, j_in = j, it_in = it;
+  if (use_cache && k_stop == q) {
+    const uint32_t k0 = lane0_of(k), l0 = lane0_of(live), p0 = lane0_of(pathr), j0 = lane0_of(j);
+    const bool shared = go && k == k0 && live == l0 && pathr == p0 && j == j0;
+    if (!__any(!shared)) {
+      if (cache.valid && k0 == cache.k && l0 == cache.live && p0 == cache.pathr &&
+          j0 == cache.j) {
+        const uint32_t dD = D - cache.D, dM = M - cache.M;
+        const uint32_t far = flip_distance(D, cache.D) + flip_distance(M, cache.M) + 2u;
+        const bool ok = dD == lane0_of(dD) && dM == lane0_of(dM) && far <= cache.margin &&
+                        it + cache.iters <= cap;
+        if (!__any(!ok)) {
+          for (uint32_t kk = k0; kk < q; ++kk) {
+            const uint32_t jj = cache.levels[kk];
+            emit(kk, jj == 0 ? b : -(int)jj);
+          }
+          k = q;
+          it += cache.iters;
+          go = false;
+          replayed = true;
+          ++cache.replays;
+        }
+      }
+      record = !replayed;
+    }
+  }
+  if (record) {
+    for (; it < cap && go; ++it) move(TrackOn{});
+    // usable if it ran to the end without incident and no lane can have left the others
+    const uint32_t apart = flip_distance(D_in, lane0_of(D_in)) + flip_distance(M_in, lane0_of(M_in)) + 2u;
+    const uint32_t m_all = wave_min32(margin);
+    const uint32_t apart_all = wave_max32(apart);
+    const bool fine = k == q && anom == 0;
+    cache.valid = (uint32_t)(!__any(!fine) && apart_all <= m_all);
+    cache.k = k_in; cache.live = live_in; cache.pathr = pathr_in; cache.j = j_in;
+    cache.D = D_in; cache.M = M_in;
+    cache.margin = m_all;
+    cache.iters = it - it_in;
+  } else {
+    for (; it < cap && go; ++it) move(TrackOff{});
   }
   anomaly = anomaly || anom != 0 || (k < k_stop);
   return k;
@@ -308,9 +431,12 @@ __device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, u
 // Phase one of a rank: baseblock, receive schedule, send walk.  Writes
 // recvblock[k] to recv_row[k] and sendblock[k] to send_row[k] (bytes), returns
 // the mask of violation rounds still to be filled in, the baseblock and flags.
+// `cache` is the wavefront's lockstep record; use_cache may be true only when
+// all 64 lanes make this call together (a full tile).
 __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
                                                         int8_t *recv_row, int8_t *send_row,
-                                                        int &b_out, uint32_t &flags) {
+                                                        int &b_out, uint32_t &flags,
+                                                        LockstepCache &cache, bool use_cache) {
   const uint32_t q = in.q;
   flags = 0;
   const uint32_t jb = baseblock_level(in.pm1, q, v);
@@ -320,8 +446,10 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   bool anomaly = false;
   uint32_t produced;
   auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
+  // the root and rank 1 start differently: their tile runs without the record
+  const bool use = use_cache && !__any(v <= 1u);
   if (v == 1u) produced = recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
-  else produced = recv_search_fast(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
+  else produced = recv_search_fast(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv, cache, use);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
   const uint32_t viol = send_walk(in.p, in.pm1, q, v, b,
                                   [&](uint32_t k, int val) { send_row[k] = (int8_t)val; });
@@ -364,8 +492,10 @@ __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint
   bool anomaly_t = false;
   auto take = [&](uint32_t kk, int x) { if (kk == k) val = x; };
   uint32_t got;
+  LockstepCache none;
+  lockstep_cache_init(none, nullptr);
   if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
-  else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
+  else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take, none, false);
   if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
   return val;
 }
@@ -393,7 +523,9 @@ __device__ __forceinline__ uint32_t compute_rank(const Instance &in, uint32_t v,
                                                  int8_t *recv_row, int8_t *send_row,
                                                  int &b_out) {
   uint32_t flags;
-  const uint32_t viol = compute_rank_phase1(in, v, recv_row, send_row, b_out, flags);
+  LockstepCache none;
+  lockstep_cache_init(none, nullptr);
+  const uint32_t viol = compute_rank_phase1(in, v, recv_row, send_row, b_out, flags, none, false);
   return flags | resolve_by_search(in, v, viol, send_row);
 }
 

@@ -104,6 +104,12 @@ __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint6
 // LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
 // rows of 2q bytes (rounded up to 16 bytes).
 __host__ __device__ inline uint32_t slice_words(uint32_t q) { return ((kWave * 2u * q + 15u) / 16u) * 4u; }
+// ... plus, for wavefronts that work through runs of tiles, 32 bytes for the
+// record of the lockstep stretch (LockstepCache::levels), after all slices.
+constexpr uint32_t kRecordWords = 8u;
+__host__ __device__ inline uint32_t lone_block_words(uint32_t q) {
+  return kWavesPerBlock * (slice_words(q) + kRecordWords);
+}
 
 constexpr uint32_t kQueueCap = 4u * kBlock;       // at most four violations per rank
 
@@ -118,7 +124,8 @@ template <bool kShare>
 __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_begin,
                                                uint64_t n_ranks, uint64_t tile, uint64_t n_tiles,
                                                uint32_t *slices, uint32_t slice_w, uint32_t pitch,
-                                               uint32_t send_off, uint32_t lane, uint32_t wave) {
+                                               uint32_t send_off, uint32_t lane, uint32_t wave,
+                                               LockstepCache &cache, bool use_cache) {
   __shared__ uint2 queue[kShare ? kQueueCap : 1u];   // {to-processor, k | LDS byte offset << 8}
   __shared__ uint32_t queue_n;
   TileState st;
@@ -132,7 +139,8 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
   uint32_t viol = 0;
   if (lane < st.n_valid) {
     st.v = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
-    viol = compute_rank_phase1(in, st.v, recv_row, send_row, st.b, st.flags);
+    viol = compute_rank_phase1(in, st.v, recv_row, send_row, st.b, st.flags,
+                               cache, use_cache && st.n_valid == (uint32_t)kWave);
   }
   if (kShare) {
     if (threadIdx.x == 0) queue_n = 0;
@@ -190,7 +198,7 @@ constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefr
 
 // words of LDS per wavefront: slice, receive rows of the tile above, queue
 __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
-  return slice_words(q) + 16u * q + 2u * kDeferCap;
+  return slice_words(q) + 16u * q + 2u * kDeferCap + kRecordWords;
 }
 
 __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
@@ -240,10 +248,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   uint64_t t_lo, t_hi;
   tile_run(n_tiles, t_lo, t_hi);
+  LockstepCache record;
   if (!kShare) {
+    lockstep_cache_init(record, reinterpret_cast<uint8_t *>(lds_dyn + kWavesPerBlock * slice_w +
+                                                            wave * kRecordWords));
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<false>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                            slice_w, pitch, send_off, lane, wave);
+                                            slice_w, pitch, send_off, lane, wave, record, true);
       copy_out(tile * kWave, st.n_valid);
       wave_lds_sync();                         // the slice is rewritten next
     }
@@ -252,6 +263,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
   uint2 *queue = reinterpret_cast<uint2 *>(words + slice_w + 16u * q);
+  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(words + slice_w + 16u * q + 2u * kDeferCap));
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
   for (uint64_t tile = t_hi; tile-- > t_lo;) {
@@ -261,7 +273,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     int b = 0;
     if (lane < n_valid) {
       v = virtual_rank(in, (uint32_t)(prm.r_begin + row0 + lane));
-      viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags);
+      viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags,
+                                 record, n_valid == (uint32_t)kWave);
     }
     wave_lds_sync();
     uint32_t open = 0;
@@ -327,9 +340,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
+  LockstepCache record;                      // used by wavefronts that work through runs of tiles
+  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(lds_dyn + kWavesPerBlock * slice_w +
+                                                          wave * kRecordWords));
   auto one_tile = [&](uint64_t tile) {
     const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                           slice_w, 2u * q, q, lane, wave);
+                                           slice_w, 2u * q, q, lane, wave, record, !kShare);
     acc_flags |= st.flags;
     if (lane < st.n_valid) {
       const uint32_t r = (uint32_t)(prm.r_begin + tile * kWave + lane);
@@ -781,7 +797,7 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
   } else {
     const int grid = persistent_grid(blocks);
     if (grid < 0) return BCAST_EHIP;
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL(k_schedules<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
@@ -803,10 +819,10 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   const int grid = persistent_grid((n + kBlock - 1) / kBlock);
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
@@ -827,10 +843,10 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint6
   const int grid = persistent_grid((n + kBlock - 1) / kBlock);
   if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
-    const size_t lds = (size_t)kWavesPerBlock * slice_words(prm.q) * 4u;
+    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;

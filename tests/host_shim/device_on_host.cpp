@@ -15,7 +15,12 @@ static uint32_t q_of(uint32_t p) {
   return q;
 }
 
+static uint64_t g_replays = 0;
+
 extern "C" {
+
+// searches of the last shim_schedules_tiles call that replayed a lockstep record
+uint64_t shim_last_replays(void) { return g_replays; }
 
 // rows: m rows of 2q int32 (recv then send) for the physical ranks given.
 // flags_out/hash_out (may be NULL): per-rank flags and row hash.
@@ -50,6 +55,10 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   uint64_t borrowed = 0;
   // tiles from the highest down, two buffers, as a wavefront does within its run
   static int8_t tiles[2][64 * 62];
+  // one lockstep record per lane position: lane l sees ranks 64 apart, as on the GPU
+  static LockstepCache caches[64];
+  static uint8_t levels[64][32];
+  for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], levels[l]);
   uint32_t cur = 0, n_valid_next = 0;
   const int8_t *next_recv = nullptr;
   const uint64_t n_tiles = (n + 63) / 64;
@@ -63,7 +72,8 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
       vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
       viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
-                                       tile + lane * 2 * q + q, b[lane], fl[lane]);
+                                       tile + lane * 2 * q + q, b[lane], fl[lane],
+                                       caches[lane], n_valid == 64);
     }
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
       int8_t *recv_row = tile + lane * 2 * q;
@@ -87,6 +97,8 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     cur ^= 1u;
   }
   if (n_from_tile) *n_from_tile = borrowed;
+  g_replays = 0;
+  for (int l = 0; l < 64; ++l) g_replays += caches[l].replays;
   return (int)q;
 }
 

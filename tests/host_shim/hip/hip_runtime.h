@@ -14,3 +14,4 @@ static inline int __popc(unsigned x) { return __builtin_popcount(x); }
 // cross-lane operations for a wavefront of one lane
 static inline int __any(int pred) { return pred != 0; }
 static inline int __shfl_xor(int v, int, int) { return v; }
+static inline int __builtin_amdgcn_readfirstlane(int v) { return v; }

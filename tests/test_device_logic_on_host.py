@@ -37,6 +37,7 @@ def shim():
     lib.shim_schedules_tiles.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                          ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
+    lib.shim_last_replays.restype = ctypes.c_uint64
     return lib
 
 
@@ -141,3 +142,25 @@ def test_edge_check_rows(shim):
             want_r ^= a
             want_s ^= b
         assert (int(xr.value), int(xs.value)) == (want_r, want_s)
+
+
+def test_replayed_lockstep_stretch_equals_the_search(shim):
+    # Ranks 64 apart (one lane of consecutive tiles) mostly arrive at the lockstep stretch of the
+    # receive search in the same shared state; the kernels then replay a recorded stretch instead
+    # of searching.  Whatever is replayed must equal Algorithm 5, everywhere a record can be taken
+    # over: long stretches of consecutive ranks at both ends and in the middle of several p.
+    replays = 0
+    cases = [(2**31 - 1, 0, 2**30 - 30000, 60000), (2**31 - 1, 12345, 2**31 - 1 - 50000, 50000),
+             (2**31 - 1, 0, 0, 40000), (1000003, 0, 0, 120000), (1000003, 999999, 880000, 120003),
+             (805306373, 7, 402653000, 50000), (2**30 + 1, 2**29, 2**29 - 20000, 40000),
+             (65537, 1, 0, 65537), (4099, 0, 0, 4099), (3 * 2**20, 5, 2**20 - 10000, 30000)]
+    for p, root, a, n in cases:
+        rows, flags, _, _ = shim_tiles(shim, p, root, a, n)
+        replays_here = int(shim.shim_last_replays())
+        want = oracle.schedules(p, root=root, r_begin=a, r_end=a + n, send_mode=1)
+        assert np.array_equal(rows, want), (p, root, a, n)
+        assert not flags.any()
+        replays += replays_here
+        if p > 10**6:
+            assert replays_here > n // 4, (p, replays_here)     # the record is actually used
+    assert replays > 200000

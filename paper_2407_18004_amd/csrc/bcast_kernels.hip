@@ -249,12 +249,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   uint64_t t_lo, t_hi;
   tile_run(n_tiles, t_lo, t_hi);
   LockstepCache record;
+  const bool long_run = t_hi - t_lo >= 3u;     // recording costs more than it saves on two tiles
   if (!kShare) {
     lockstep_cache_init(record, reinterpret_cast<uint8_t *>(lds_dyn + kWavesPerBlock * slice_w +
                                                             wave * kRecordWords));
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<false>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                            slice_w, pitch, send_off, lane, wave, record, true);
+                                            slice_w, pitch, send_off, lane, wave, record, long_run);
       copy_out(tile * kWave, st.n_valid);
       wave_lds_sync();                         // the slice is rewritten next
     }
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     if (lane < n_valid) {
       v = virtual_rank(in, (uint32_t)(prm.r_begin + row0 + lane));
       viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags,
-                                 record, n_valid == (uint32_t)kWave);
+                                 record, long_run && n_valid == (uint32_t)kWave);
     }
     wave_lds_sync();
     uint32_t open = 0;

@@ -127,43 +127,6 @@ __device__ __forceinline__ uint32_t recv_search(uint32_t p, uint32_t pm1, uint32
   return k;
 }
 
-// Algorithm 6 without its violations: writes sendblock[k] through emit for
-// k = q-1 .. 0 and returns the mask of rounds k whose entry must instead be
-// taken from the receive schedule of the to-processor.  All lanes are in the
-// same round k, so skip[k] and skip[k-1] are scalars.
-template <typename Emit>
-__device__ __forceinline__ uint32_t send_walk(uint32_t p, uint32_t pm1, uint32_t q,
-                                              uint32_t v, int b, Emit emit) {
-  if (q == 0) return 0;
-  uint32_t viol = 0;
-  uint32_t rp = v, e = p;
-  int c = b;
-  for (uint32_t k = q - 1; k >= 1; --k) {
-    const uint32_t skk = skip_at_level(pm1, q - k);
-    const uint32_t skm = skip_at_level(pm1, q - k + 1);
-    const bool k_is_1 = k == 1;
-    const bool lower = rp < skk;
-    const uint32_t s1 = rp + skk;
-    const uint32_t em = e - skk;               // meaningful in the upper part only
-    const bool ok_lower = (s1 < e) || (e < skm) || (k_is_1 && b > 0);
-    const bool ok_upper = k_is_1 || (rp > skk) || (em < skm) || (s1 <= e);
-    const bool bad = lower ? !ok_lower : !ok_upper;
-    viol = (viol << 1) | (uint32_t)bad;         // round k ends up at bit k - 1
-    c = lower ? c : (int)k - (int)q;
-    e = lower ? (e < skk ? e : skk) : em;
-    const uint32_t rm = rp - skk;               // wraps above rp in the lower part
-    rp = rm < rp ? rm : rp;
-    emit(k, c);
-  }
-  emit(0u, b - (int)q);
-  viol <<= 1;
-  if (v == 0) {                                 // the root sends block k in round k
-    for (uint32_t k = 0; k < q; ++k) emit(k, (int)k);
-    viol = 0;
-  }
-  return viol;
-}
-
 // Published SplitMix64 output function.
 __device__ __forceinline__ uint64_t sm64(uint64_t z) {
   z += 0x9E3779B97F4A7C15ull;
@@ -185,6 +148,95 @@ __device__ __forceinline__ Instance make_instance(uint32_t p, uint32_t q, uint32
 // (r - root + p) mod p without leaving 32 bits (Section 2: renumbering).
 __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r) {
   return r >= in.root ? r - in.root : r + (in.p - in.root);
+}
+
+// One pass over the levels j = 1 .. q, i.e. over skip[q-1] down to skip[0],
+// serves three purposes at once, because all three walk down the same skips:
+//   Algorithm 3: rem is what is left of v; a skip is taken when it still fits;
+//     the last one taken (it brings rem to 0) is the baseblock's.
+//   Algorithm 6 (kSend): its r' is the same rem, so "lower part" = skip not
+//     taken; e, c and the violation tests as printed, round k = q - j.  While c
+//     still stands for the baseblock, which is not known before the pass ends,
+//     the entries written are placeholders (see leading_rounds).
+//   Descent of the receive search (see recv_ascent): W = D - 2; a level is
+//     pushed when its skip <= W, accepted for round 0 when skip = W + 1, and the
+//     baseblock's level is not in the list.  A level is the baseblock's exactly
+//     when it is taken and brings rem to 0, which is known on the spot.
+struct TopDown {
+  uint32_t rem, jb;
+  bool closed;                      // the level before this one was the baseblock's
+  int W;
+  uint32_t pathr, anom;
+  uint32_t e;
+  int c;
+  uint32_t viol;                    // round k at bit k - 1 after the last round
+};
+
+constexpr int kPendingB = 0;        // placeholder for "c = baseblock" inside the pass
+
+__device__ __forceinline__ TopDown top_down_start(uint32_t p, uint32_t v) {
+  const bool is_root = v == 0;
+  TopDown s;
+  s.rem = v; s.jb = 0; s.closed = is_root;
+  // W = D - 2 as a signed number; after the accept W = -1, which neither fits
+  // nor hits any more.  pathr holds the pending calls with level j at bit
+  // 31 - j, so that the deepest one is the lowest set bit.  For v >= 2 the first
+  // call (index q, skip p) is always recursive: the walk starts below it.
+  s.W = (int)((is_root ? p : v) - 2u);
+  s.pathr = is_root ? 0u : 0x80000000u;
+  s.anom = 0;
+  s.e = p; s.c = kPendingB; s.viol = 0;
+  return s;
+}
+
+template <bool kSend, typename EmitSend>
+__device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_t j, TopDown &s,
+                                               EmitSend emit_send) {
+  const uint32_t sk = skip_at_level(pm1, j);            // the same in all lanes: a scalar
+  const bool lower = s.rem < sk;
+  const uint32_t rem_new = lower ? s.rem : s.rem - sk;
+  if (kSend && j < q) {                                 // round k = q - j >= 1 of Algorithm 6
+    const uint32_t k = q - j;
+    const uint32_t skm = skip_at_level(pm1, j + 1u);    // skip[k - 1]
+    const bool k_is_1 = k == 1u;
+    const uint32_t s1 = s.rem + sk;
+    const uint32_t em = s.e - sk;                       // meaningful in the upper part only
+    // at k = 1: the baseblock is not 0 iff skip[0] will not be taken
+    const bool ok_lower = (s1 < s.e) || (s.e < skm) || (k_is_1 && rem_new == 0u);
+    const bool ok_upper = k_is_1 || (s.rem > sk) || (em < skm) || (s1 <= s.e);
+    const bool bad = lower ? !ok_lower : !ok_upper;
+    s.viol = (s.viol << 1) | (uint32_t)bad;
+    s.c = lower ? s.c : (int)k - (int)q;
+    s.e = lower ? (s.e < sk ? s.e : sk) : em;
+    emit_send(k, s.c);
+  }
+  const bool closes = !lower && rem_new == 0u;          // this level is the baseblock's
+  s.jb = lower ? s.jb : j;
+  s.rem = rem_new;
+  const int ski = (int)sk;
+  const int t = s.W - ski;
+  const bool take = !closes && t >= -1;                 // push (t >= 0) or accept (t = -1)
+  // The call made for this index would look at the index again (skip + 1 <=
+  // D - skip) and that look must fail.  It does whenever the level above was
+  // looked at (skip[e+1] <= 2 skip[e]); only right below the baseblock's
+  // level, which is not in the list, the test is made explicitly.
+  s.anom |= (uint32_t)(s.closed && take && t >= 0 && ski <= t + 1);
+  s.W = take ? t : s.W;
+  s.pathr |= take ? (0x80000000u >> j) : 0u;            // the accepted level too, for now
+  s.closed = closes;
+}
+
+// Rounds of Algorithm 6 at the top whose entry is the baseblock itself: those
+// before the first skip that fits into v (c has not been set by an upper part
+// yet).  Returns the first level taken, 1 <= jt <= q, for v >= 1.
+__device__ __forceinline__ uint32_t first_level_taken(uint32_t pm1, uint32_t v) {
+  // smallest j >= 1 with (pm1 >> j) + 1 <= v, i.e. (pm1 >> j) <= x = v - 1 < pm1
+  const uint32_t x = v - 1u;
+  const uint32_t len_p = 32u - (uint32_t)__clz((int)pm1);
+  const uint32_t len_x = x == 0u ? 0u : 32u - (uint32_t)__clz((int)x);
+  const uint32_t j1 = len_p - len_x;                   // (pm1 >> j1) has the length of x
+  const uint32_t jt = (pm1 >> j1) <= x ? j1 : j1 + 1u;
+  return jt == 0u ? 1u : jt;
 }
 
 // Cross-lane helpers for values that must be the same in all lanes.
@@ -267,31 +319,17 @@ __device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
 //    differences between the lanes of the recording tile, shows that its lanes
 //    did make the same moves.  `use_cache` = false: no replay; when it is true,
 //    all lanes of the wavefront must be in the call.
+//
+// The descent is made by the caller (top_down_level, together with Algorithms 3
+// and 6, which walk over the same levels): W, pathr and anom_in are its result.
 template <typename Emit>
-__device__ __forceinline__ uint32_t recv_search_fast(uint32_t p, uint32_t pm1, uint32_t q,
-                                                     uint32_t v, uint32_t jb, uint32_t k_last,
-                                                     bool &anomaly, Emit emit,
-                                                     LockstepCache &cache, bool use_cache) {
-  const bool is_root = v == 0;
+__device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32_t q,
+                                                uint32_t jb, uint32_t k_last, int W,
+                                                uint32_t pathr, uint32_t anom_in,
+                                                bool &anomaly, Emit emit,
+                                                LockstepCache &cache, bool use_cache) {
   const int b = (int)q - (int)jb;
-  // Descent.  W = D - 2 as a signed number; after the accept W = -1, which
-  // neither fits nor hits any more.  `pathr` holds the pending calls with level
-  // j at bit 31 - j, so that the deepest one is the lowest set bit.
-  int W = (int)((is_root ? p : v) - 2u);
-  uint32_t pathr = is_root ? 0u : 0x80000000u;
-  uint32_t anom = 0;
-  for (uint32_t j = 1; j <= q; ++j) {
-    const int sk = (int)skip_at_level(pm1, j);           // uniform: scalar
-    const int t = W - sk;
-    const bool take = j != jb && t >= -1;                 // push (t >= 0) or accept (t = -1)
-    // The call made for this index would look at the index again (skip + 1 <=
-    // D - skip) and that look must fail.  It does whenever the level above was
-    // looked at (skip[e+1] <= 2 skip[e]); only right below the baseblock's
-    // level, which is not in the list, the test is made explicitly.
-    if (__any(j == jb + 1u)) anom |= (uint32_t)(j == jb + 1u && take && t >= 0 && sk <= t + 1);
-    W = take ? t : W;
-    pathr |= take ? (0x80000000u >> j) : 0u;              // the accepted level too, for now
-  }
+  uint32_t anom = anom_in;
   const bool hit = W == -1;
   // The accept, if any, was the last level taken: the deepest bit of pathr.
   const uint32_t jd = hit ? 31u - (uint32_t)(__ffs((int)pathr) - 1) : 0u;
@@ -439,20 +477,33 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
                                                         LockstepCache &cache, bool use_cache) {
   const uint32_t q = in.q;
   flags = 0;
-  const uint32_t jb = baseblock_level(in.pm1, q, v);
+  b_out = 0;
+  if (q == 0) return 0;
+  auto put_send = [&](uint32_t k, int val) { send_row[k] = (int8_t)val; };
+  TopDown s = top_down_start(in.p, v);
+  for (uint32_t j = 1; j <= q; ++j) top_down_level<true>(in.pm1, q, j, s, put_send);
+  const uint32_t jb = s.jb;
   const int b = (int)q - (int)jb;
   b_out = b;
-  if (q == 0) return 0;
+  uint32_t viol = s.viol << 1;                  // round k at bit k
+  if (v == 0) {                                 // the root sends block k in round k
+    for (uint32_t k = 0; k < q; ++k) send_row[k] = (int8_t)k;
+    viol = 0;
+  } else {
+    // the rounds above the first skip taken send the baseblock; so does round 0 (Condition 4)
+    const uint32_t jt = first_level_taken(in.pm1, v);
+    for (uint32_t j = 1; j < jt; ++j) send_row[q - j] = (int8_t)b;
+    send_row[0] = (int8_t)(b - (int)q);
+  }
   bool anomaly = false;
   uint32_t produced;
   auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
   // the root and rank 1 start differently: their tile runs without the record
   const bool use = use_cache && !__any(v <= 1u);
   if (v == 1u) produced = recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
-  else produced = recv_search_fast(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv, cache, use);
+  else produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
+                              cache, use);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
-  const uint32_t viol = send_walk(in.p, in.pm1, q, v, b,
-                                  [&](uint32_t k, int val) { send_row[k] = (int8_t)val; });
   if (__popc(viol) > 4) flags |= BCAST_F_VIOLATIONS;
   return viol;
 }
@@ -487,7 +538,9 @@ __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint3
 __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint32_t k,
                                             uint32_t &flags) {
   const uint32_t q = in.q;
-  const uint32_t jbt = baseblock_level(in.pm1, q, t);
+  TopDown s = top_down_start(in.p, t);
+  for (uint32_t j = 1; j <= q; ++j) top_down_level<false>(in.pm1, q, j, s, [](uint32_t, int) {});
+  const uint32_t jbt = s.jb;
   int val = 0;
   bool anomaly_t = false;
   auto take = [&](uint32_t kk, int x) { if (kk == k) val = x; };
@@ -495,7 +548,7 @@ __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint
   LockstepCache none;
   lockstep_cache_init(none, nullptr);
   if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
-  else got = recv_search_fast(in.p, in.pm1, q, t, jbt, k, anomaly_t, take, none, false);
+  else got = recv_ascent(in.p, in.pm1, q, jbt, k, s.W, s.pathr, s.anom, anomaly_t, take, none, false);
   if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
   return val;
 }

@@ -150,6 +150,16 @@ __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r)
   return r >= in.root ? r - in.root : r + (in.p - in.root);
 }
 
+struct TrackOff { static constexpr bool value = false; };
+struct TrackOn { static constexpr bool value = true; };
+
+// How far the difference x - y of a test "x >= y" is from flipping: the test
+// keeps its outcome as long as the difference moves by no more than this.
+__device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
+  const int dxy = (int)(x - y);                 // all operands are below 2^31
+  return (uint32_t)(dxy ^ (dxy >> 31));           // d for d >= 0, -1 - d for d < 0
+}
+
 // One pass over the levels j = 1 .. q, i.e. over skip[q-1] down to skip[0],
 // serves three purposes at once, because all three walk down the same skips:
 //   Algorithm 3: rem is what is left of v; a skip is taken when it still fits;
@@ -189,18 +199,30 @@ __device__ __forceinline__ TopDown top_down_start(uint32_t p, uint32_t v) {
   return s;
 }
 
-template <bool kSend, typename EmitSend>
+//
+// kTrack: every test whose outcome depends on v also lowers `margin` to its
+// flip distance (tests between constants of the instance are left out; a test
+// that is not consulted may be included, which only makes the margin smaller).
+template <bool kSend, bool kTrack, typename EmitSend>
 __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_t j, TopDown &s,
-                                               EmitSend emit_send) {
+                                               uint32_t &margin, EmitSend emit_send) {
+  auto see = [&](uint32_t x, uint32_t y) {
+    if (kTrack) { const uint32_t fd = flip_distance(x, y); margin = fd < margin ? fd : margin; }
+  };
   const uint32_t sk = skip_at_level(pm1, j);            // the same in all lanes: a scalar
+  see(s.rem, sk);
   const bool lower = s.rem < sk;
   const uint32_t rem_new = lower ? s.rem : s.rem - sk;
+  see(0u, rem_new);                                     // rem_new == 0
   if (kSend && j < q) {                                 // round k = q - j >= 1 of Algorithm 6
     const uint32_t k = q - j;
     const uint32_t skm = skip_at_level(pm1, j + 1u);    // skip[k - 1]
     const bool k_is_1 = k == 1u;
     const uint32_t s1 = s.rem + sk;
     const uint32_t em = s.e - sk;                       // meaningful in the upper part only
+    see(s1, s.e);
+    see(s.e, s1);
+    see(s.rem, sk + 1u);
     // at k = 1: the baseblock is not 0 iff skip[0] will not be taken
     const bool ok_lower = (s1 < s.e) || (s.e < skm) || (k_is_1 && rem_new == 0u);
     const bool ok_upper = k_is_1 || (s.rem > sk) || (em < skm) || (s1 <= s.e);
@@ -215,6 +237,9 @@ __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_
   s.rem = rem_new;
   const int ski = (int)sk;
   const int t = s.W - ski;
+  see((uint32_t)(t + 1), 0u);
+  see((uint32_t)t, 0u);
+  see((uint32_t)(t + 1), sk);
   const bool take = !closes && t >= -1;                 // push (t >= 0) or accept (t = -1)
   // The call made for this index would look at the index again (skip + 1 <=
   // D - skip) and that look must fail.  It does whenever the level above was
@@ -237,6 +262,16 @@ __device__ __forceinline__ uint32_t first_level_taken(uint32_t pm1, uint32_t v) 
   const uint32_t j1 = len_p - len_x;                   // (pm1 >> j1) has the length of x
   const uint32_t jt = (pm1 >> j1) <= x ? j1 : j1 + 1u;
   return jt == 0u ? 1u : jt;
+}
+
+// Number of levels at the top whose skip is at least kTopSkip (levels 1 .. n).
+constexpr uint32_t kTopSkip = 4096u;
+__device__ __forceinline__ uint32_t top_level_count(uint32_t pm1, uint32_t q) {
+  if (pm1 < kTopSkip) return 0u;
+  // skip_at_level(j) >= kTopSkip  <=>  (pm1 >> j) >= kTopSkip - 1
+  uint32_t n = 32u - (uint32_t)__clz((int)(pm1 / (kTopSkip - 1u)));   // first j with pm1 >> j < kTopSkip - 1
+  n = n == 0u ? 0u : n - 1u;
+  return n < q ? n : q;
 }
 
 // Cross-lane helpers for values that must be the same in all lanes.
@@ -271,21 +306,22 @@ struct LockstepCache {
   uint32_t margin;                  // how far D and M may move before a test flips
   uint32_t iters;                   // iterations the stretch took
   uint32_t replays;                 // tiles that took the record (statistics)
+  // Record of the pass over the top levels (skip >= kTopSkip), see compute_rank_phase1:
+  // the state after them as a function of v, the same in all lanes, and how far v may move.
+  uint32_t top_valid, top_levels;
+  uint32_t top_v;                   // this lane's v when the record was taken
+  uint32_t top_T, top_Tw;           // v - rem and v - W
+  uint32_t top_jb, top_pathr, top_e, top_viol, top_bits;   // bits: closed, anom
+  int top_c;
+  uint32_t top_margin;
+  uint32_t top_replays;
 };
 
 __device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint8_t *levels) {
   c.levels = levels;
   c.valid = 0; c.k = 0; c.live = 0; c.pathr = 0; c.j = 0; c.D = 0; c.M = 0; c.margin = 0; c.iters = 0; c.replays = 0;
-}
-
-struct TrackOff { static constexpr bool value = false; };
-struct TrackOn { static constexpr bool value = true; };
-
-// How far the difference x - y of a test "x >= y" is from flipping: the test
-// keeps its outcome as long as the difference moves by no more than this.
-__device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
-  const int dxy = (int)(x - y);                 // all operands are below 2^31
-  return (uint32_t)(dxy ^ (dxy >> 31));           // d for d >= 0, -1 - d for d < 0
+  c.top_valid = 0; c.top_levels = 0; c.top_v = 0; c.top_T = 0; c.top_Tw = 0; c.top_jb = 0; c.top_pathr = 0;
+  c.top_e = 0; c.top_viol = 0; c.top_bits = 0; c.top_c = 0; c.top_margin = 0; c.top_replays = 0;
 }
 
 // The receive search again, in the form the kernels use: same state and same
@@ -481,7 +517,49 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   if (q == 0) return 0;
   auto put_send = [&](uint32_t k, int val) { send_row[k] = (int8_t)val; };
   TopDown s = top_down_start(in.p, v);
-  for (uint32_t j = 1; j <= q; ++j) top_down_level<true>(in.pm1, q, j, s, put_send);
+  // the root and rank 1 start differently: their tile runs without the record
+  const bool use = use_cache && !__any(v <= 1u);
+  uint32_t j = 1, unused = 0;
+  // Top levels.  64 consecutive ranks, and the ranks of the next tiles, make the same
+  // decisions at the large skips; after them rem = v - T and W = v - Tw with the same T and
+  // Tw, and everything else is a constant.  A tile that runs these levels records that state
+  // (if it is indeed the same in all lanes) and how far v may move before any test flips; a
+  // later tile whose ranks are closer than that takes the state over.  Its rows still hold
+  // the top rounds of Algorithm 6 from the recording tile, which are what it would write.
+  const uint32_t n_top = use ? top_level_count(in.pm1, q) : 0u;
+  if (n_top >= 4u) {
+    const uint32_t dv = v - cache.top_v;
+    const bool near = cache.top_valid != 0u && cache.top_levels == n_top && dv == lane0_of(dv) &&
+                      flip_distance(v, cache.top_v) + 1u <= cache.top_margin;
+    if (!__any(!near)) {
+      s.rem = v - cache.top_T;
+      s.W = (int)(v - cache.top_Tw);
+      s.jb = cache.top_jb; s.pathr = cache.top_pathr; s.e = cache.top_e; s.c = cache.top_c;
+      s.viol = cache.top_viol;
+      s.closed = (cache.top_bits & 1u) != 0u;
+      s.anom = cache.top_bits >> 1;
+      ++cache.top_replays;
+    } else {
+      uint32_t margin = 0xFFFFFFFFu;
+      for (; j <= n_top; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
+      const uint32_t T = v - s.rem, Tw = v - (uint32_t)s.W;
+      const uint32_t bits = (uint32_t)s.closed | (s.anom << 1);
+      const bool same = T == lane0_of(T) && Tw == lane0_of(Tw) && s.jb == lane0_of(s.jb) &&
+                        s.pathr == lane0_of(s.pathr) && s.e == lane0_of(s.e) &&
+                        (uint32_t)s.c == lane0_of((uint32_t)s.c) && s.viol == lane0_of(s.viol) &&
+                        bits == lane0_of(bits);
+      cache.top_valid = (uint32_t)!__any(!same);
+      cache.top_levels = n_top;
+      cache.top_v = v;
+      cache.top_T = lane0_of(T); cache.top_Tw = lane0_of(Tw); cache.top_jb = lane0_of(s.jb);
+      cache.top_pathr = lane0_of(s.pathr); cache.top_e = lane0_of(s.e);
+      cache.top_c = (int)lane0_of((uint32_t)s.c); cache.top_viol = lane0_of(s.viol);
+      cache.top_bits = lane0_of(bits);
+      cache.top_margin = wave_min32(margin);
+    }
+    j = n_top + 1u;
+  }
+  for (; j <= q; ++j) top_down_level<true, false>(in.pm1, q, j, s, unused, put_send);
   const uint32_t jb = s.jb;
   const int b = (int)q - (int)jb;
   b_out = b;
@@ -498,8 +576,6 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   bool anomaly = false;
   uint32_t produced;
   auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
-  // the root and rank 1 start differently: their tile runs without the record
-  const bool use = use_cache && !__any(v <= 1u);
   if (v == 1u) produced = recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
   else produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
                               cache, use);
@@ -539,7 +615,9 @@ __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint
                                             uint32_t &flags) {
   const uint32_t q = in.q;
   TopDown s = top_down_start(in.p, t);
-  for (uint32_t j = 1; j <= q; ++j) top_down_level<false>(in.pm1, q, j, s, [](uint32_t, int) {});
+  uint32_t unused = 0;
+  for (uint32_t j = 1; j <= q; ++j)
+    top_down_level<false, false>(in.pm1, q, j, s, unused, [](uint32_t, int) {});
   const uint32_t jbt = s.jb;
   int val = 0;
   bool anomaly_t = false;

@@ -15,12 +15,14 @@ static uint32_t q_of(uint32_t p) {
   return q;
 }
 
-static uint64_t g_replays = 0;
+static uint64_t g_replays = 0, g_top_replays = 0;
 
 extern "C" {
 
 // searches of the last shim_schedules_tiles call that replayed a lockstep record
 uint64_t shim_last_replays(void) { return g_replays; }
+// ... and that took over the state after the top levels
+uint64_t shim_last_top_replays(void) { return g_top_replays; }
 
 // rows: m rows of 2q int32 (recv then send) for the physical ranks given.
 // flags_out/hash_out (may be NULL): per-rank flags and row hash.
@@ -53,20 +55,22 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
   uint64_t borrowed = 0;
-  // tiles from the highest down, two buffers, as a wavefront does within its run
-  static int8_t tiles[2][64 * 62];
-  // one lockstep record per lane position: lane l sees ranks 64 apart, as on the GPU
+  // tiles from the highest down, as a wavefront does within its run: one slice that is reused
+  // (rows of the previous tile stay where they are until they are overwritten) and a copy of the
+  // receive rows of the tile above
+  static int8_t tile[64 * 62];
+  static int8_t above[64 * 31];
+  memset(tile, 0x55, sizeof tile);
+  // one record per lane position: lane l sees ranks 64 apart, as on the GPU
   static LockstepCache caches[64];
   static uint8_t levels[64][32];
   for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], levels[l]);
-  uint32_t cur = 0, n_valid_next = 0;
+  uint32_t n_valid_next = 0;
   const int8_t *next_recv = nullptr;
   const uint64_t n_tiles = (n + 63) / 64;
   for (uint64_t ti = n_tiles; ti-- > 0;) {
     const uint64_t row0 = ti * 64;
     const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
-    int8_t *tile = tiles[cur];
-    memset(tile, 0x55, 64 * 62);
     uint32_t viol[64], fl[64], vr[64];
     int b[64];
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
@@ -78,7 +82,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     for (uint32_t lane = 0; lane < n_valid; ++lane) {
       int8_t *recv_row = tile + lane * 2 * q;
       const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
-                                               2 * q, 2 * q, lane, n_valid, n_valid_next);
+                                               2 * q, q, lane, n_valid, n_valid_next);
       borrowed += (uint64_t)__popc(viol[lane] ^ open);
       fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
     }
@@ -91,14 +95,15 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
       digest_rank(in, (uint32_t)(r_begin + i), vr[lane], b[lane], recv_row, h, fl2);
       if (flags_out) flags_out[i] = fl[lane] | fl2;
       if (hash_out) hash_out[i] = h;
+      for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
     }
-    next_recv = tile;
+    next_recv = above;
     n_valid_next = n_valid;
-    cur ^= 1u;
   }
   if (n_from_tile) *n_from_tile = borrowed;
   g_replays = 0;
-  for (int l = 0; l < 64; ++l) g_replays += caches[l].replays;
+  g_top_replays = 0;
+  for (int l = 0; l < 64; ++l) { g_replays += caches[l].replays; g_top_replays += caches[l].top_replays; }
   return (int)q;
 }
 

@@ -38,6 +38,7 @@ def shim():
                                          ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_last_replays.restype = ctypes.c_uint64
+    lib.shim_last_top_replays.restype = ctypes.c_uint64
     return lib
 
 
@@ -157,10 +158,12 @@ def test_replayed_lockstep_stretch_equals_the_search(shim):
     for p, root, a, n in cases:
         rows, flags, _, _ = shim_tiles(shim, p, root, a, n)
         replays_here = int(shim.shim_last_replays())
+        top_here = int(shim.shim_last_top_replays())
         want = oracle.schedules(p, root=root, r_begin=a, r_end=a + n, send_mode=1)
         assert np.array_equal(rows, want), (p, root, a, n)
         assert not flags.any()
         replays += replays_here
         if p > 10**6:
             assert replays_here > n // 4, (p, replays_here)     # the record is actually used
+            assert top_here > n // 4, (p, top_here)
     assert replays > 200000

@@ -190,29 +190,30 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
 // just finished (64 rows of q bytes), so a violation of Algorithm 6 whose
 // to-processor is at most one tile up is answered from LDS.  The others are not
 // searched for on the spot, where they would occupy a few lanes of an otherwise
-// idle wavefront per tile: the row leaves with the entry still open, {row, k}
-// goes into a queue in LDS, and whenever 64 are waiting, and once more at the
+// idle wavefront per tile: the row leaves with the entry still open, its place
+// (row within the run << 5 | k) goes into a queue in LDS, and whenever 64 are waiting, and once more at the
 // end of the run, one search per lane fills them in and stores the entries
 // straight into the table.
 constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefront
 
 // words of LDS per wavefront: slice, receive rows of the tile above, queue
 __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
-  return slice_words(q) + 16u * q + 2u * kDeferCap + kRecordWords;
+  return slice_words(q) + 16u * q + kDeferCap + kRecordWords;
 }
 
 __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
-                                               const uint2 *queue, uint32_t lo, uint32_t hi,
-                                               uint32_t lane) {
+                                               const uint32_t *queue, uint64_t run_row0,
+                                               uint32_t lo, uint32_t hi, uint32_t lane) {
   // The rows were stored by this wavefront; they must have landed before single
   // entries of them are overwritten.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (lo + lane < hi) {
-    const uint2 item = queue[lo + lane];             // {row in the launch, k}
-    const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + item.x));
+    const uint32_t item = queue[lo + lane];
+    const uint64_t row = run_row0 + (item >> 5);     // row in the launch
+    const uint32_t k = item & 31u;
+    const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + row));
     uint32_t fl = 0;
-    prm.send[(uint64_t)item.x * (uint64_t)prm.ld + item.y] =
-        search_entry(in, to_processor(in, v, item.y), item.y, fl);
+    prm.send[row * (uint64_t)prm.ld + k] = search_entry(in, to_processor(in, v, k), k, fl);
   }
 }
 
@@ -263,8 +264,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   }
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
-  uint2 *queue = reinterpret_cast<uint2 *>(words + slice_w + 16u * q);
-  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(words + slice_w + 16u * q + 2u * kDeferCap));
+  uint32_t *queue = words + slice_w + 16u * q;
+  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(words + slice_w + 16u * q + kDeferCap));
+  const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
   for (uint64_t tile = t_hi; tile-- > t_lo;) {
@@ -282,18 +284,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     if (lane < n_valid)
       open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                 pitch, q, lane, n_valid, n_valid_above);
+    // a queue entry holds the row within the run in 27 bits: runs are far shorter than that,
+    // and a tile beyond it would simply search on the spot
+    const bool can_defer = row0 + kWave - run_row0 <= (1ull << 27);
     while (__any(open != 0)) {
       const bool has = open != 0;
       const uint64_t who = __ballot(has);
-      const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
+      const uint32_t slot = can_defer ? n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull))
+                                      : kDeferCap;
       if (has) {
         const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
         open &= open - 1u;
-        if (slot < kDeferCap) queue[slot] = make_uint2((uint32_t)(row0 + lane), k);
+        if (slot < kDeferCap) queue[slot] = ((uint32_t)(row0 + lane - run_row0) << 5) | k;
         else send_row[k] = (int8_t)search_entry(in, to_processor(in, v, k), k, flags);
       }
-      const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
-      n_queued = n_new < kDeferCap ? n_new : kDeferCap;
+      if (can_defer) {
+        const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
+        n_queued = n_new < kDeferCap ? n_new : kDeferCap;
+      }
     }
     wave_lds_sync();
     copy_out(row0, n_valid);
@@ -301,12 +309,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
     n_valid_above = n_valid;
     while (n_queued >= (uint32_t)kWave) {
-      deferred_flush(in, prm, queue, n_queued - kWave, n_queued, lane);
+      deferred_flush(in, prm, queue, run_row0, n_queued - kWave, n_queued, lane);
       n_queued -= kWave;
     }
     wave_lds_sync();                           // slice and queue are rewritten next
   }
-  deferred_flush(in, prm, queue, 0u, n_queued, lane);
+  deferred_flush(in, prm, queue, run_row0, 0u, n_queued, lane);
 }
 
 // ------------------------------------------------------------------- digest

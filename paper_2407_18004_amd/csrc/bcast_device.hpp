@@ -295,33 +295,37 @@ __device__ __forceinline__ uint32_t wave_max32(uint32_t x) {
   return x;
 }
 
-// What a wavefront remembers of the lockstep stretch of one tile, to replay it
-// on later tiles of its run (see recv_search_fast).  `levels` points at 32 bytes
-// of the wavefront's own LDS; everything except D and M is the same in all lanes.
-struct LockstepCache {
-  uint8_t *levels;                  // level accepted for round k, k = k_entry .. q-1
-  uint32_t valid;
-  uint32_t k, live, pathr, j;       // state on entry to the stretch
-  uint32_t D, M;                    // this lane's D and M on entry
-  uint32_t margin;                  // how far D and M may move before a test flips
-  uint32_t iters;                   // iterations the stretch took
-  uint32_t replays;                 // tiles that took the record (statistics)
-  // Record of the pass over the top levels (skip >= kTopSkip), see compute_rank_phase1:
-  // the state after them as a function of v, the same in all lanes, and how far v may move.
-  uint32_t top_valid, top_levels;
-  uint32_t top_v;                   // this lane's v when the record was taken
-  uint32_t top_T, top_Tw;           // v - rem and v - W
-  uint32_t top_jb, top_pathr, top_e, top_viol, top_bits;   // bits: closed, anom
-  int top_c;
-  uint32_t top_margin;
-  uint32_t top_replays;
+// What a wavefront remembers from one tile of its run to replay on the next
+// ones: the lockstep stretch of the receive search (see recv_ascent) and the
+// state after the top levels of the pass (see compute_rank_phase1).  Everything
+// that is the same in all lanes lives in kRecordWords words of the wavefront's
+// own LDS (`mem`), so that it costs no registers between tiles; D, M and top_v
+// are this lane's own.
+enum RecordWord : uint32_t {
+  kRecLevels = 0,                   // 32 bytes: level accepted for round k, k = k_entry .. q-1
+  kRecValid = 8, kRecK, kRecLive, kRecPathr, kRecJ,   // state on entry to the stretch
+  kRecMargin,                       // how far D and M may move before a test flips
+  kRecIters,                        // iterations the stretch took
+  kRecReplays,                      // tiles that took the record (statistics)
+  kTopValid, kTopLevels,            // the top levels: valid, how many
+  kTopT, kTopTw,                    // v - rem and v - W after them
+  kTopJb, kTopPathr, kTopE, kTopViol, kTopBits, kTopC,   // bits: closed, anom
+  kTopMargin, kTopReplays,
+  kRecordWords = 32
 };
 
-__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint8_t *levels) {
-  c.levels = levels;
-  c.valid = 0; c.k = 0; c.live = 0; c.pathr = 0; c.j = 0; c.D = 0; c.M = 0; c.margin = 0; c.iters = 0; c.replays = 0;
-  c.top_valid = 0; c.top_levels = 0; c.top_v = 0; c.top_T = 0; c.top_Tw = 0; c.top_jb = 0; c.top_pathr = 0;
-  c.top_e = 0; c.top_viol = 0; c.top_bits = 0; c.top_c = 0; c.top_margin = 0; c.top_replays = 0;
+struct LockstepCache {
+  uint32_t *mem;
+  uint32_t D, M;                    // this lane's D and M on entry to the recorded stretch
+  uint32_t top_v;                   // this lane's v when the top levels were recorded
+};
+
+__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *mem) {
+  c.mem = mem;
+  c.D = 0; c.M = 0; c.top_v = 0;
+  if (mem != nullptr) {
+    mem[kRecValid] = 0; mem[kRecReplays] = 0; mem[kTopValid] = 0; mem[kTopReplays] = 0;
+  }
 }
 
 // The receive search again, in the form the kernels use: same state and same
@@ -441,7 +445,7 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
       see(D, sk1);
       if (D >= sk1) {                       // accept e for round k
         emit(k, jj == 0 ? b : -(int)jj);
-        if (kTrack) cache.levels[k] = (uint8_t)jj;
+        if (kTrack) reinterpret_cast<uint8_t *>(cache.mem)[k] = (uint8_t)jj;
         live ^= 1u << jj;
         see(sk1, t + 2u);
         M = sk1 > t + 1u ? sk1 : t + 1u;
@@ -462,22 +466,22 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
     const uint32_t k0 = lane0_of(k), l0 = lane0_of(live), p0 = lane0_of(pathr), j0 = lane0_of(j);
     const bool shared = go && k == k0 && live == l0 && pathr == p0 && j == j0;
     if (!__any(!shared)) {
-      if (cache.valid && k0 == cache.k && l0 == cache.live && p0 == cache.pathr &&
-          j0 == cache.j) {
+      if (cache.mem[kRecValid] && k0 == cache.mem[kRecK] && l0 == cache.mem[kRecLive] && p0 == cache.mem[kRecPathr] &&
+          j0 == cache.mem[kRecJ]) {
         const uint32_t dD = D - cache.D, dM = M - cache.M;
         const uint32_t far = flip_distance(D, cache.D) + flip_distance(M, cache.M) + 2u;
-        const bool ok = dD == lane0_of(dD) && dM == lane0_of(dM) && far <= cache.margin &&
-                        it + cache.iters <= cap;
+        const bool ok = dD == lane0_of(dD) && dM == lane0_of(dM) && far <= cache.mem[kRecMargin] &&
+                        it + cache.mem[kRecIters] <= cap;
         if (!__any(!ok)) {
           for (uint32_t kk = k0; kk < q; ++kk) {
-            const uint32_t jj = cache.levels[kk];
+            const uint32_t jj = reinterpret_cast<const uint8_t *>(cache.mem)[kk];
             emit(kk, jj == 0 ? b : -(int)jj);
           }
           k = q;
-          it += cache.iters;
+          it += cache.mem[kRecIters];
           go = false;
           replayed = true;
-          ++cache.replays;
+          cache.mem[kRecReplays] = cache.mem[kRecReplays] + 1u;
         }
       }
       record = !replayed;
@@ -490,11 +494,11 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
     const uint32_t m_all = wave_min32(margin);
     const uint32_t apart_all = wave_max32(apart);
     const bool fine = k == q && anom == 0;
-    cache.valid = (uint32_t)(!__any(!fine) && apart_all <= m_all);
-    cache.k = k_in; cache.live = live_in; cache.pathr = pathr_in; cache.j = j_in;
+    cache.mem[kRecValid] = (uint32_t)(!__any(!fine) && apart_all <= m_all);
+    cache.mem[kRecK] = k_in; cache.mem[kRecLive] = live_in; cache.mem[kRecPathr] = pathr_in; cache.mem[kRecJ] = j_in;
     cache.D = D_in; cache.M = M_in;
-    cache.margin = m_all;
-    cache.iters = it - it_in;
+    cache.mem[kRecMargin] = m_all;
+    cache.mem[kRecIters] = it - it_in;
   } else {
     for (; it < cap && go; ++it) move(TrackOff{});
   }
@@ -529,16 +533,16 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   const uint32_t n_top = use ? top_level_count(in.pm1, q) : 0u;
   if (n_top >= 4u) {
     const uint32_t dv = v - cache.top_v;
-    const bool near = cache.top_valid != 0u && cache.top_levels == n_top && dv == lane0_of(dv) &&
-                      flip_distance(v, cache.top_v) + 1u <= cache.top_margin;
+    const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == lane0_of(dv) &&
+                      flip_distance(v, cache.top_v) + 1u <= cache.mem[kTopMargin];
     if (!__any(!near)) {
-      s.rem = v - cache.top_T;
-      s.W = (int)(v - cache.top_Tw);
-      s.jb = cache.top_jb; s.pathr = cache.top_pathr; s.e = cache.top_e; s.c = cache.top_c;
-      s.viol = cache.top_viol;
-      s.closed = (cache.top_bits & 1u) != 0u;
-      s.anom = cache.top_bits >> 1;
-      ++cache.top_replays;
+      s.rem = v - cache.mem[kTopT];
+      s.W = (int)(v - cache.mem[kTopTw]);
+      s.jb = cache.mem[kTopJb]; s.pathr = cache.mem[kTopPathr]; s.e = cache.mem[kTopE]; s.c = (int)cache.mem[kTopC];
+      s.viol = cache.mem[kTopViol];
+      s.closed = (cache.mem[kTopBits] & 1u) != 0u;
+      s.anom = cache.mem[kTopBits] >> 1;
+      cache.mem[kTopReplays] = cache.mem[kTopReplays] + 1u;
     } else {
       uint32_t margin = 0xFFFFFFFFu;
       for (; j <= n_top; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
@@ -548,14 +552,14 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
                         s.pathr == lane0_of(s.pathr) && s.e == lane0_of(s.e) &&
                         (uint32_t)s.c == lane0_of((uint32_t)s.c) && s.viol == lane0_of(s.viol) &&
                         bits == lane0_of(bits);
-      cache.top_valid = (uint32_t)!__any(!same);
-      cache.top_levels = n_top;
+      cache.mem[kTopValid] = (uint32_t)!__any(!same);
+      cache.mem[kTopLevels] = n_top;
       cache.top_v = v;
-      cache.top_T = lane0_of(T); cache.top_Tw = lane0_of(Tw); cache.top_jb = lane0_of(s.jb);
-      cache.top_pathr = lane0_of(s.pathr); cache.top_e = lane0_of(s.e);
-      cache.top_c = (int)lane0_of((uint32_t)s.c); cache.top_viol = lane0_of(s.viol);
-      cache.top_bits = lane0_of(bits);
-      cache.top_margin = wave_min32(margin);
+      cache.mem[kTopT] = lane0_of(T); cache.mem[kTopTw] = lane0_of(Tw); cache.mem[kTopJb] = lane0_of(s.jb);
+      cache.mem[kTopPathr] = lane0_of(s.pathr); cache.mem[kTopE] = lane0_of(s.e);
+      cache.mem[kTopC] = lane0_of((uint32_t)s.c); cache.mem[kTopViol] = lane0_of(s.viol);
+      cache.mem[kTopBits] = lane0_of(bits);
+      cache.mem[kTopMargin] = wave_min32(margin);
     }
     j = n_top + 1u;
   }

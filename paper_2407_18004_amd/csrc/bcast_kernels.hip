@@ -104,9 +104,8 @@ __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint6
 // LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
 // rows of 2q bytes (rounded up to 16 bytes).
 __host__ __device__ inline uint32_t slice_words(uint32_t q) { return ((kWave * 2u * q + 15u) / 16u) * 4u; }
-// ... plus, for wavefronts that work through runs of tiles, 32 bytes for the
-// record of the lockstep stretch (LockstepCache::levels), after all slices.
-constexpr uint32_t kRecordWords = 8u;
+// ... plus, for wavefronts that work through runs of tiles, kRecordWords words
+// for what they carry from tile to tile (LockstepCache::mem), after all slices.
 __host__ __device__ inline uint32_t lone_block_words(uint32_t q) {
   return kWavesPerBlock * (slice_words(q) + kRecordWords);
 }
@@ -252,8 +251,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;     // recording costs more than it saves on two tiles
   if (!kShare) {
-    lockstep_cache_init(record, reinterpret_cast<uint8_t *>(lds_dyn + kWavesPerBlock * slice_w +
-                                                            wave * kRecordWords));
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<false>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
                                             slice_w, pitch, send_off, lane, wave, record, long_run);
@@ -265,7 +263,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
   uint32_t *queue = words + slice_w + 16u * q;
-  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(words + slice_w + 16u * q + kDeferCap));
+  lockstep_cache_init(record, words + slice_w + 16u * q + kDeferCap);
   const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
@@ -350,8 +348,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
   LockstepCache record;                      // used by wavefronts that work through runs of tiles
-  lockstep_cache_init(record, reinterpret_cast<uint8_t *>(lds_dyn + kWavesPerBlock * slice_w +
-                                                          wave * kRecordWords));
+  lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
   auto one_tile = [&](uint64_t tile) {
     const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
                                            slice_w, 2u * q, q, lane, wave, record, !kShare);

@@ -63,8 +63,8 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   memset(tile, 0x55, sizeof tile);
   // one record per lane position: lane l sees ranks 64 apart, as on the GPU
   static LockstepCache caches[64];
-  static uint8_t levels[64][32];
-  for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], levels[l]);
+  static uint32_t record_mem[64][kRecordWords];
+  for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem[l]);
   uint32_t n_valid_next = 0;
   const int8_t *next_recv = nullptr;
   const uint64_t n_tiles = (n + 63) / 64;
@@ -103,7 +103,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   if (n_from_tile) *n_from_tile = borrowed;
   g_replays = 0;
   g_top_replays = 0;
-  for (int l = 0; l < 64; ++l) { g_replays += caches[l].replays; g_top_replays += caches[l].top_replays; }
+  for (int l = 0; l < 64; ++l) { g_replays += caches[l].mem[kRecReplays]; g_top_replays += caches[l].mem[kTopReplays]; }
   return (int)q;
 }
 

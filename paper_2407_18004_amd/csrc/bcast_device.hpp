@@ -17,7 +17,7 @@
 namespace bcast {
 
 constexpr uint32_t kEndLevel = 0xFFFFFFFFu;
-constexpr uint32_t kLockstepSkip = 1024u;   // see recv_search_fast: where the ascent re-synchronises
+constexpr uint32_t kLockstepSkip = 1024u;   // see recv_ascent: where the ascent re-synchronises
 
 // skip[q - j]
 __device__ __forceinline__ uint32_t skip_at_level(uint32_t pm1, uint32_t j) {
@@ -33,7 +33,8 @@ __device__ __forceinline__ uint32_t next_level(uint32_t live, uint32_t j) {
 // Algorithm 3 in level form: the level of the baseblock of virtual rank v,
 // i.e. q - b.  The greedy walk takes skip[k] whenever it still fits; the last
 // skip taken closes the sum and is the smallest index of the canonical skip
-// sequence.  v = 0 takes nothing and yields level 0 (b = q).
+// sequence.  v = 0 takes nothing and yields level 0 (b = q).  (On its own, for
+// callers that want the baseblock only; the kernels get it from top_down_level.)
 __device__ __forceinline__ uint32_t baseblock_level(uint32_t pm1, uint32_t q, uint32_t v) {
   uint32_t rem = v, jb = 0;
   for (uint32_t j = 1; j <= q; ++j) {

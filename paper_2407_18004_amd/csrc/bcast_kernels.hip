@@ -82,17 +82,8 @@ struct SchedParams {
   int layout;
 };
 
-// How the tiles of a launch are dealt out.
-//  kShare = false: every wavefront works alone through its own run of tiles;
-//    only wavefront-level ordering of LDS is needed.  Used when Algorithm 6 has
-//    no violations to speak of.
-//  kShare = true: the four wavefronts of a workgroup take four consecutive tiles
-//    at a time ("unit").  A violation of Algorithm 6 asks for a row of a higher
-//    rank: the same tile or the next one, i.e. the slice of the wavefront next
-//    door, answers most of them.  What is left (targets far away or beyond the
-//    unit) goes into a queue in LDS and is worked off by as few lanes as there
-//    are entries, instead of by one nearly empty wavefront per tile.  All
-//    threads of a workgroup make the same number of calls (workgroup barriers).
+// How the tiles of a launch are dealt out: every wavefront works through one
+// contiguous run of tiles, alone (only wavefront-level ordering of LDS is needed).
 __device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint64_t &t_hi) {
   // wavefront w of W takes tiles [w n / W, (w + 1) n / W): runs differ by one tile at most
   const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
@@ -110,26 +101,22 @@ __host__ __device__ inline uint32_t lone_block_words(uint32_t q) {
   return kWavesPerBlock * (slice_words(q) + kRecordWords);
 }
 
-constexpr uint32_t kQueueCap = 4u * kBlock;       // at most four violations per rank
-
 struct TileState {
   uint32_t v, n_valid, flags;
   int b;
 };
 
 // Computes the rows of tile `tile` (one per lane) into the wavefront's slice,
-// violations resolved.  slices: the workgroup's four slices, slice_w words each.
-template <bool kShare>
+// violations of Algorithm 6 resolved from rows of the same tile or else by
+// search on the spot: for p = 2^q and 2^q - 1, which have next to none.
+// slices: the workgroup's four slices, slice_w words each.
 __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_begin,
                                                uint64_t n_ranks, uint64_t tile, uint64_t n_tiles,
                                                uint32_t *slices, uint32_t slice_w, uint32_t pitch,
                                                uint32_t send_off, uint32_t lane, uint32_t wave,
                                                LockstepCache &cache, bool use_cache) {
-  __shared__ uint2 queue[kShare ? kQueueCap : 1u];   // {to-processor, k | LDS byte offset << 8}
-  __shared__ uint32_t queue_n;
   TileState st;
   st.v = 0; st.flags = 0; st.b = 0;
-  int8_t *base = reinterpret_cast<int8_t *>(slices);
   int8_t *tile_recv = reinterpret_cast<int8_t *>(slices + wave * slice_w);
   int8_t *recv_row = tile_recv + lane * pitch;
   int8_t *send_row = recv_row + send_off;
@@ -141,46 +128,13 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
     viol = compute_rank_phase1(in, st.v, recv_row, send_row, st.b, st.flags,
                                cache, use_cache && st.n_valid == (uint32_t)kWave);
   }
-  if (kShare) {
-    if (threadIdx.x == 0) queue_n = 0;
-    __syncthreads();
-  } else {
-    wave_lds_sync();
-  }
+  wave_lds_sync();
   if (lane < st.n_valid) {
-    const bool next_here = kShare && wave + 1u < kWavesPerBlock && tile + 1u < n_tiles;
-    const uint64_t left_next = next_here ? n_ranks - (row0 + kWave) : 0u;
-    const uint32_t n_valid_next = left_next < kWave ? (uint32_t)left_next : kWave;
-    const int8_t *next_recv =
-        next_here ? reinterpret_cast<const int8_t *>(slices + (wave + 1u) * slice_w) : nullptr;
-    uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, next_recv, pitch, pitch,
-                                       lane, st.n_valid, n_valid_next);
-    if (kShare) {
-      while (open != 0) {
-        const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
-        open &= open - 1u;
-        const uint32_t slot = atomicAdd(&queue_n, 1u);
-        if (slot < kQueueCap)
-          queue[slot] = make_uint2(to_processor(in, st.v, k),
-                                   k | ((uint32_t)(send_row + k - base) << 8));
-        else                                   // cannot happen with at most four per rank
-          send_row[k] = (int8_t)search_entry(in, to_processor(in, st.v, k), k, st.flags);
-      }
-    } else {
-      st.flags |= resolve_by_search(in, st.v, open, send_row);
-    }
+    const uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, nullptr, pitch, pitch,
+                                             lane, st.n_valid, 0u);
+    st.flags |= resolve_by_search(in, st.v, open, send_row);
   }
-  if (kShare) {
-    __syncthreads();
-    const uint32_t n_queued = queue_n < kQueueCap ? queue_n : kQueueCap;
-    for (uint32_t e = threadIdx.x; e < n_queued; e += kBlock) {
-      const uint2 item = queue[e];
-      base[item.y >> 8] = (int8_t)search_entry(in, item.x, item.y & 255u, st.flags);
-    }
-    __syncthreads();
-  } else {
-    wave_lds_sync();
-  }
+  wave_lds_sync();
   return st;
 }
 
@@ -253,8 +207,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   if (!kShare) {
     lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
-      const TileState st = tile_rows<false>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                            slice_w, pitch, send_off, lane, wave, record, long_run);
+      const TileState st = tile_rows(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
+                                     pitch, send_off, lane, wave, record, long_run);
       copy_out(tile * kWave, st.n_valid);
       wave_lds_sync();                         // the slice is rewritten next
     }
@@ -334,6 +288,15 @@ __global__ void k_edges_init(uint64_t *xors) {
 
 // kEdges = false: digest and flags.  kEdges = true: the two XOR sums of the
 // edge check go to prm.digest[0] and prm.digest[1]; flags are not touched.
+//
+// kShare (p with violations): runs of tiles from the top down with the rows of
+// the tile above in LDS, as in k_schedules<true>.  A row can only be hashed
+// when it is complete, so here whole rows are deferred: a rank that still has
+// an open violation after the look into the two tiles is put into the queue
+// (row within the run), and whenever 64 are waiting, and at the end of the run,
+// each lane computes one such rank again from scratch, violations by search,
+// and hashes it.  That is 2 to 3 ranks in 64; it costs the slice its rows, so
+// the record of the top levels starts again after a batch.
 template <bool kShare, bool kEdges>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
@@ -342,39 +305,100 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
   const uint32_t slice_w = slice_words(q);
-  const int8_t *row = reinterpret_cast<const int8_t *>(lds_dyn + wave * slice_w) + lane * 2u * q;
+  uint32_t *words = lds_dyn + wave * (kShare ? deferred_wave_words(q) : slice_w);
+  int8_t *tile_recv = reinterpret_cast<int8_t *>(words);
+  int8_t *recv_row = tile_recv + lane * 2u * q;
+  int8_t *send_row = recv_row + q;
   const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
   uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
-  LockstepCache record;                      // used by wavefronts that work through runs of tiles
-  lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
-  auto one_tile = [&](uint64_t tile) {
-    const TileState st = tile_rows<kShare>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn,
-                                           slice_w, 2u * q, q, lane, wave, record, !kShare);
-    acc_flags |= st.flags;
-    if (lane < st.n_valid) {
-      const uint32_t r = (uint32_t)(prm.r_begin + tile * kWave + lane);
-      if (kEdges) {
-        edge_rank(in, r, row, acc, acc2);
-      } else {
-        uint64_t h;
-        uint32_t fl2;
-        digest_rank(in, r, st.v, st.b, row, h, fl2);
-        acc ^= h;
-        acc_flags |= fl2;
-      }
+  auto take_row = [&](uint32_t r, uint32_t v, int b) {       // the lane's row is complete
+    if (kEdges) {
+      edge_rank(in, r, recv_row, acc, acc2);
+    } else {
+      uint64_t h;
+      uint32_t fl2;
+      digest_rank(in, r, v, b, recv_row, h, fl2);
+      acc ^= h;
+      acc_flags |= fl2;
     }
-    if (!kShare) wave_lds_sync();            // the slice is rewritten next
   };
-  if (kShare) {
-    const uint64_t n_units = (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    for (uint64_t unit = blockIdx.x; unit < n_units; unit += gridDim.x)
-      one_tile(unit * kWavesPerBlock + wave);
+  uint64_t t_lo, t_hi;
+  tile_run(n_tiles, t_lo, t_hi);
+  LockstepCache record;
+  const bool long_run = t_hi - t_lo >= 3u;
+  if (!kShare) {
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
+    for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
+      const TileState st = tile_rows(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
+                                     2u * q, q, lane, wave, record, long_run);
+      acc_flags |= st.flags;
+      if (lane < st.n_valid) take_row((uint32_t)(prm.r_begin + tile * kWave + lane), st.v, st.b);
+      wave_lds_sync();                         // the slice is rewritten next
+    }
   } else {
-    uint64_t t_lo, t_hi;
-    tile_run(n_tiles, t_lo, t_hi);
-    for (uint64_t tile = t_lo; tile < t_hi; ++tile) one_tile(tile);
+    int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
+    uint32_t *queue = words + slice_w + 16u * q;
+    lockstep_cache_init(record, words + slice_w + 16u * q + kDeferCap);
+    const uint64_t run_row0 = t_lo * kWave;
+    uint32_t n_queued = 0;                     // the same in all lanes; at most 63 between tiles
+    uint32_t n_valid_above = 0;
+    uint64_t tile = t_hi;
+    // One pass of the loop is either the next tile of the run or a batch of deferred ranks
+    // (64 of them, or what is left once the tiles are done), one rank per lane in both cases.
+    for (;;) {
+      const bool batch = n_queued >= (uint32_t)kWave || (tile == t_lo && n_queued != 0u);
+      if (!batch && tile == t_lo) break;
+      uint64_t row = 0;                        // the lane's rank, as a row of the launch
+      uint32_t n_here;                         // lanes with a rank in this pass
+      if (batch) {
+        n_here = n_queued < (uint32_t)kWave ? n_queued : (uint32_t)kWave;
+        if (lane < n_here) row = run_row0 + queue[n_queued - n_here + lane];
+      } else {
+        --tile;
+        const uint64_t row0 = tile * kWave;
+        n_here = prm.n_ranks - row0 < kWave ? (uint32_t)(prm.n_ranks - row0) : kWave;
+        row = row0 + lane;
+      }
+      const uint32_t r = (uint32_t)(prm.r_begin + row);
+      uint32_t v = 0, viol = 0, flags = 0;
+      int b = 0;
+      if (lane < n_here) {
+        v = virtual_rank(in, r);
+        viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags, record,
+                                   !batch && long_run && n_here == (uint32_t)kWave);
+      }
+      acc_flags |= flags;
+      wave_lds_sync();
+      uint32_t open = 0;
+      if (lane < n_here) {
+        if (batch) {                           // no neighbours here: every violation by search
+          acc_flags |= resolve_by_search(in, v, viol, send_row);
+        } else {
+          open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
+                                    2u * q, q, lane, n_here, n_valid_above);
+        }
+        if (open == 0) take_row(r, v, b);
+      }
+      if (batch) {
+        n_queued -= n_here;
+        record.mem[kTopValid] = 0;             // the rows of the last tile are gone
+      } else {
+        const uint64_t who = __ballot(open != 0);
+        const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
+        if (open != 0) {
+          if (slot < kDeferCap) queue[slot] = (uint32_t)(row - run_row0);
+          else acc_flags |= BCAST_F_SEARCH;    // cannot happen: at most 63 + 64 entries
+        }
+        const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
+        n_queued = n_new < kDeferCap ? n_new : kDeferCap;
+        if (lane < n_here)
+          for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+        n_valid_above = n_here;
+      }
+      wave_lds_sync();                         // slice and queue are rewritten next
+    }
   }
   acc = wave_xor64(acc);
   if (kEdges) acc2 = wave_xor64(acc2);
@@ -822,12 +846,14 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   prm.p = p; prm.q = (uint32_t)q; prm.root = root;
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = digest; prm.flags = flags;
-  const int grid = persistent_grid((n + kBlock - 1) / kBlock);
-  if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
+    const int grid = run_grid((n + kWave - 1) / kWave);
+    if (grid < 0) return BCAST_EHIP;
+    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
+    const int grid = persistent_grid((n + kBlock - 1) / kBlock);
+    if (grid < 0) return BCAST_EHIP;
     const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
@@ -846,12 +872,14 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint6
   prm.p = p; prm.q = (uint32_t)q; prm.root = root;
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = xors; prm.flags = nullptr;
-  const int grid = persistent_grid((n + kBlock - 1) / kBlock);
-  if (grid < 0) return BCAST_EHIP;
   if (keep_next_tile(p)) {
-    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
+    const int grid = run_grid((n + kWave - 1) / kWave);
+    if (grid < 0) return BCAST_EHIP;
+    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
+    const int grid = persistent_grid((n + kBlock - 1) / kBlock);
+    if (grid < 0) return BCAST_EHIP;
     const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }

@@ -175,6 +175,9 @@ def test_long_runs_with_deferred_violations(p, root, a, b):
     torch.cuda.synchronize()
     got = tab.cpu().numpy()
     assert np.array_equal(got[:, :2 * q], want) and (got[:, 2 * q:] == 1234).all()
+    # the same ranks through the digest and the edge check (whole rows deferred there)
+    assert gpu_digest(p, root, a, b) == oracle.digest(p, root, a, b, send_mode=1)
+    assert gpu_edgecheck(p, root, a, b) == oracle.edgecheck(p, root, a, b, send_mode=1)
     # send by definition on a seeded sample
     ranks = np.sort(workloads.streamed_sample_ranks(512, seed=11, p=n).astype(np.int64)) + a
     assert np.array_equal(want[ranks - a], oracle.schedules_ranks(p, root, ranks.astype(np.uint32), send_mode=0))

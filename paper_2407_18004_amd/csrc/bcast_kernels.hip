@@ -545,7 +545,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 // ---------------------------------------------------------------- simulator
 
 constexpr int kSimBlock = 128;
-constexpr int kSimMaxQ = 31;
 
 struct SimParams {
   uint32_t p, q, n, n_words, x;
@@ -580,9 +579,13 @@ __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rou
 // then checks that what arrives (its send entry) is for a block it still has.
 template <bool kReverse>
 __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
-  __shared__ int32_t st_recv[kSimMaxQ][kSimBlock];
-  __shared__ int32_t st_send[kSimMaxQ][kSimBlock];
-  __shared__ int32_t st_from[kSimMaxQ][kSimBlock];   // sendblock[k] of the from-processor
+  // three [q][kSimBlock] arrays, sized at launch: the lane's recvblock and sendblock and the
+  // sendblock[k] of its from-processor
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  typedef int32_t (*Staged)[kSimBlock];
+  Staged st_recv = reinterpret_cast<Staged>(lds_dyn);
+  Staged st_send = st_recv + prm.q;
+  Staged st_from = st_send + prm.q;
   const uint32_t lane_b = threadIdx.x;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t root_idx = blockIdx.y;
@@ -976,8 +979,9 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   prm.roots = d_roots; prm.sched = sched; prm.table = table;
   prm.possession = possession; prm.verdict = verdict;
   dim3 grid((p + kSimBlock - 1) / kSimBlock, n_roots);
-  if (reverse) hipLaunchKernelGGL(k_simulate<true>, grid, dim3(kSimBlock), 0, st, prm);
-  else hipLaunchKernelGGL(k_simulate<false>, grid, dim3(kSimBlock), 0, st, prm);
+  const size_t lds = (size_t)3u * prm.q * kSimBlock * sizeof(int32_t);
+  if (reverse) hipLaunchKernelGGL(k_simulate<true>, grid, dim3(kSimBlock), lds, st, prm);
+  else hipLaunchKernelGGL(k_simulate<false>, grid, dim3(kSimBlock), lds, st, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 

@@ -129,4 +129,9 @@ void shim_digest_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row,
   digest_rank(in, r, v, b, buf, *hash, *flags);
 }
 
+// index helpers of the pass over the levels, for direct checks against Algorithm 2's skips
+uint32_t shim_first_level_taken(uint32_t p, uint32_t v) { return first_level_taken(p - 1u, v); }
+uint32_t shim_top_level_count(uint32_t p) { return top_level_count(p - 1u, q_of(p)); }
+uint32_t shim_top_skip(void) { return kTopSkip; }
+
 }  // extern "C"

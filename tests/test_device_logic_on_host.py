@@ -167,3 +167,23 @@ def test_replayed_lockstep_stretch_equals_the_search(shim):
             assert replays_here > n // 4, (p, replays_here)     # the record is actually used
             assert top_here > n // 4, (p, top_here)
     assert replays > 200000
+
+
+def test_level_helpers_against_the_skips(shim):
+    # first level whose skip fits into v, and the number of levels with a skip of at least the
+    # threshold, against skip[] of Algorithm 2 (level j is skip[q - j])
+    rng = np.random.default_rng(3)
+    top_skip = int(shim.shim_top_skip())
+    ps = [2, 3, 5, 17, 100, 4095, 4096, 4097, 8191, 8192, 65537, 1000003, 2**30 + 1, 2**31 - 1]
+    ps += [int(x) for x in rng.integers(2, 2**31 - 1, size=40)]
+    for p in ps:
+        sk = oracle.skips(p)
+        q = len(sk) - 1
+        want_top = sum(1 for j in range(1, q + 1) if sk[q - j] >= top_skip)
+        assert int(shim.shim_top_level_count(p)) == want_top, p
+        vs = {1, 2, 3, p - 1, p // 2, max(1, p // 2 - 1), min(p - 1, p // 2 + 1)}
+        vs |= {int(s) for s in sk[:-1]} | {int(s) - 1 for s in sk[:-1] if s > 1} | {min(p - 1, int(s) + 1) for s in sk[:-1]}
+        vs |= {int(x) for x in rng.integers(1, p, size=20)}
+        for v in sorted(x for x in vs if 1 <= x < p):
+            want = next(j for j in range(1, q + 1) if sk[q - j] <= v)
+            assert int(shim.shim_first_level_taken(p, v)) == want, (p, v)

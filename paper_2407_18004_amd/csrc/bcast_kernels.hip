@@ -74,9 +74,14 @@ __device__ __forceinline__ void tile_out(const uint32_t *lds_words, int32_t *dst
 
 // ---------------------------------------------------------------- schedules
 
+struct RunSplit {
+  uint32_t base, extra;            // tiles / wavefronts of the grid, and the remainder
+};
+
 struct SchedParams {
   uint32_t p, q, root;
   uint64_t r_begin, n_ranks;
+  RunSplit runs;
   int32_t *recv, *send;
   int64_t ld;
   int layout;
@@ -84,12 +89,16 @@ struct SchedParams {
 
 // How the tiles of a launch are dealt out: every wavefront works through one
 // contiguous run of tiles, alone (only wavefront-level ordering of LDS is needed).
-__device__ __forceinline__ void tile_run(uint64_t n_tiles, uint64_t &t_lo, uint64_t &t_hi) {
-  // wavefront w of W takes tiles [w n / W, (w + 1) n / W): runs differ by one tile at most
-  const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-  const uint64_t w = (uint64_t)blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-  t_lo = w * n_tiles / n_waves;                 // n_tiles <= 2^25, W < 2^32: no overflow
-  t_hi = (w + 1u) * n_tiles / n_waves;
+__device__ __forceinline__ void tile_run(const RunSplit &rs, uint64_t &t_lo, uint64_t &t_hi) {
+  // wavefront w takes `base` tiles, the first `extra` wavefronts one more: runs differ by one
+  // tile at most, and everything stays below the number of tiles (< 2^32)
+  // the wavefront's number is the same in all its lanes: say so, or the loop over the run and
+  // everything derived from it would be kept per lane
+  const uint32_t w = blockIdx.x * kWavesPerBlock +
+                     (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const uint32_t lo = w * rs.base + (w < rs.extra ? w : rs.extra);
+  t_lo = lo;
+  t_hi = lo + rs.base + (w < rs.extra ? 1u : 0u);
 }
 
 // LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
@@ -174,7 +183,7 @@ template <bool kShare>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_schedules(SchedParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
   const uint32_t slice_w = slice_words(q);
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   };
 
   uint64_t t_lo, t_hi;
-  tile_run(n_tiles, t_lo, t_hi);
+  tile_run(prm.runs, t_lo, t_hi);
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;     // recording costs more than it saves on two tiles
   if (!kShare) {
@@ -274,6 +283,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 struct DigestParams {
   uint32_t p, q, root;
   uint64_t r_begin, n_ranks;
+  RunSplit runs;
   uint64_t *digest;
   uint32_t *flags;
 };
@@ -301,7 +311,7 @@ template <bool kShare, bool kEdges>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
   const uint32_t slice_w = slice_words(q);
@@ -325,7 +335,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     }
   };
   uint64_t t_lo, t_hi;
-  tile_run(n_tiles, t_lo, t_hi);
+  tile_run(prm.runs, t_lo, t_hi);
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;
   if (!kShare) {
@@ -432,7 +442,7 @@ struct DoubleParams {
 __global__ __launch_bounds__(kBlock) void k_double(DoubleParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const uint32_t q = prm.q, q2 = q + 1u;
   const uint32_t in_w = slice_words(q), out_w = slice_words(q2);
   uint32_t *w_in = lds_dyn + wave * (in_w + 2u * out_w);
@@ -505,7 +515,7 @@ __global__ void k_u32_zero(uint32_t *x) {
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
   __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
   const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const uint64_t n_work = (uint64_t)prm.n_inst * prm.tiles_per_inst;
   for (uint64_t work = (uint64_t)blockIdx.x * kWavesPerBlock + wave; work < n_work;
        work += (uint64_t)gridDim.x * kWavesPerBlock) {
@@ -745,6 +755,15 @@ int persistent_grid(uint64_t n_blocks_wanted) {
 
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
+// Runs of tiles for a grid of `grid` workgroups (see tile_run).
+RunSplit split_runs(uint64_t n_tiles, int grid) {
+  const uint64_t n_waves = (uint64_t)grid * kWavesPerBlock;
+  RunSplit rs;
+  rs.base = (uint32_t)(n_tiles / n_waves);
+  rs.extra = (uint32_t)(n_tiles % n_waves);
+  return rs;
+}
+
 // Grid of k_schedules<true>, whose wavefronts each take one contiguous run of
 // tiles.  Long runs make the deferred violations cheap; many more workgroups
 // than fit at once even out the load, because a SIMD serves its oldest
@@ -752,10 +771,10 @@ bool launch_ok() { return hipGetLastError() == hipSuccess; }
 // of two.  Measured on MI355X: about six tiles per wavefront is best for long
 // tables, two to four when that would leave fewer than two resident sets.
 constexpr uint64_t kRunTiles = 6;
-int run_grid(uint64_t n_tiles) {
+int run_grid(uint64_t n_tiles, uint32_t resident_per_cu) {
   const int cap = persistent_grid(UINT64_MAX);                  // 64 workgroups per CU
   if (cap < 0) return -1;
-  const uint64_t one_set = (uint64_t)(cap / 64) * 8u;            // 8 workgroups per CU fit at once
+  const uint64_t one_set = (uint64_t)(cap / 64) * resident_per_cu;   // workgroups that fit at once
   const uint64_t per_wg = kWavesPerBlock;
   const uint64_t g_one = (n_tiles + per_wg - 1) / per_wg;        // one tile per wavefront
   if (g_one <= one_set) return (int)(g_one == 0 ? 1 : g_one);
@@ -824,12 +843,14 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
   const uint64_t blocks = (n + kBlock - 1) / kBlock;
   if (keep_next_tile(p)) {
     const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
-    const int grid = run_grid((n + kWave - 1) / kWave);
+    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     hipLaunchKernelGGL(k_schedules<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const int grid = persistent_grid(blocks);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL(k_schedules<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
@@ -850,13 +871,15 @@ int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = digest; prm.flags = flags;
   if (keep_next_tile(p)) {
-    const int grid = run_grid((n + kWave - 1) / kWave);
+    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const int grid = persistent_grid((n + kBlock - 1) / kBlock);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
@@ -876,13 +899,15 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint6
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = xors; prm.flags = nullptr;
   if (keep_next_tile(p)) {
-    const int grid = run_grid((n + kWave - 1) / kWave);
+    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
     const int grid = persistent_grid((n + kBlock - 1) / kBlock);
     if (grid < 0) return BCAST_EHIP;
+    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
     const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
     hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }

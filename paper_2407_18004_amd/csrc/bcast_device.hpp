@@ -48,7 +48,10 @@ __device__ __forceinline__ uint32_t baseblock_level(uint32_t pm1, uint32_t q, ui
 }
 
 // Algorithms 4 and 5: the receive search for virtual rank v, as an explicit
-// state machine instead of recursion.
+// state machine instead of recursion.  This is the search in its plain form,
+// one list element per iteration from the first call on; the kernels run the
+// reorganised form below (top_down_level + recv_ascent), which the CPU checks
+// hold against this one.
 //
 // State, in the notation of Algorithm 4 with R = p + v:
 //   D    = R - r'            distance still to cover (the frame's r')
@@ -339,13 +342,14 @@ __device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *
 //    skip = W + 1".  All lanes look at the same level in the same iteration,
 //    so the skip is a scalar and the body is a handful of instructions.
 // 2. Ascent.  What follows is an irregular mix of returns, accepts and short
-//    new descents; it runs as one branch-free step per iteration in which
-//    every lane makes whichever move its state asks for.
+//    new descents; every lane makes whichever move its state asks for.
 //
 // The first call is for index q (skip p): for v >= 2 it is always a recursive
 // call, so the walk starts below it with D = v and level 0 on the path; for
-// the root level 0 is not in the list and the walk starts with D = p.  v = 1
-// (level 0 accepted directly, D = p + 1) is left to recv_search by the caller.
+// the root level 0 is not in the list and the walk starts with D = p.  For
+// v = 1 the first call accepts index q for round 0; the same start covers it:
+// W = v - 2 = -1 reads as "accepted", no deeper level can be taken, and the
+// accepted level is the deepest bit of the path, level 0, so D = p + 1.
 //
 // 3. Replay.  Once the lanes are in lockstep, the rest of the search is a
 //    function of (k, live, path, cursor), which all lanes share, and of each
@@ -581,9 +585,8 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   bool anomaly = false;
   uint32_t produced;
   auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
-  if (v == 1u) produced = recv_search(in.p, in.pm1, q, v, jb, q - 1u, anomaly, put_recv);
-  else produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
-                              cache, use);
+  produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
+                         cache, use);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
   if (__popc(viol) > 4) flags |= BCAST_F_VIOLATIONS;
   return viol;
@@ -630,8 +633,7 @@ __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint
   uint32_t got;
   LockstepCache none;
   lockstep_cache_init(none, nullptr);
-  if (t == 1u) got = recv_search(in.p, in.pm1, q, t, jbt, k, anomaly_t, take);
-  else got = recv_ascent(in.p, in.pm1, q, jbt, k, s.W, s.pathr, s.anom, anomaly_t, take, none, false);
+  got = recv_ascent(in.p, in.pm1, q, jbt, k, s.W, s.pathr, s.anom, anomaly_t, take, none, false);
   if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
   return val;
 }

@@ -129,6 +129,27 @@ void shim_digest_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row,
   digest_rank(in, r, v, b, buf, *hash, *flags);
 }
 
+// recvblock[0..q-1] of virtual rank v by the plain form of the search (recv_search) and by the
+// form the kernels run (top_down_level + recv_ascent); returns how many entries each produced
+// (plain in the low half, reorganised in the high half) and whether either raised an anomaly
+uint32_t shim_recv_two_ways(uint32_t p, uint32_t v, int32_t *plain, int32_t *fast, uint32_t *anomalies) {
+  const uint32_t q = q_of(p);
+  const Instance in = make_instance(p, q, 0);
+  TopDown s = top_down_start(p, v);
+  uint32_t unused = 0;
+  for (uint32_t j = 1; j <= q; ++j)
+    top_down_level<false, false>(in.pm1, q, j, s, unused, [](uint32_t, int) {});
+  bool an_plain = false, an_fast = false;
+  const uint32_t n_plain = q ? recv_search(p, in.pm1, q, v, s.jb, q - 1u, an_plain,
+                                           [&](uint32_t k, int x) { plain[k] = x; }) : 0u;
+  LockstepCache none;
+  lockstep_cache_init(none, nullptr);
+  const uint32_t n_fast = q ? recv_ascent(p, in.pm1, q, s.jb, q - 1u, s.W, s.pathr, s.anom, an_fast,
+                                          [&](uint32_t k, int x) { fast[k] = x; }, none, false) : 0u;
+  *anomalies = (uint32_t)an_plain | ((uint32_t)an_fast << 1);
+  return n_plain | (n_fast << 16);
+}
+
 // index helpers of the pass over the levels, for direct checks against Algorithm 2's skips
 uint32_t shim_first_level_taken(uint32_t p, uint32_t v) { return first_level_taken(p - 1u, v); }
 uint32_t shim_top_level_count(uint32_t p) { return top_level_count(p - 1u, q_of(p)); }

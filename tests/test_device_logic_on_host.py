@@ -38,6 +38,9 @@ def shim():
                                          ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_last_replays.restype = ctypes.c_uint64
+    lib.shim_recv_two_ways.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_void_p]
+    lib.shim_recv_two_ways.restype = ctypes.c_uint32
     lib.shim_last_top_replays.restype = ctypes.c_uint64
     return lib
 
@@ -187,3 +190,22 @@ def test_level_helpers_against_the_skips(shim):
         for v in sorted(x for x in vs if 1 <= x < p):
             want = next(j for j in range(1, q + 1) if sk[q - j] <= v)
             assert int(shim.shim_first_level_taken(p, v)) == want, (p, v)
+
+
+def test_plain_and_reorganised_receive_search_agree(shim):
+    # the search one list element at a time from the first call on, and the form the kernels run,
+    # against each other and against Algorithm 5 of the oracle, rank 1 and the root included
+    rng = np.random.default_rng(11)
+    cases = [(p, v) for p in range(1, 300) for v in range(p)]
+    for p in [1000003, 2**31 - 1, 2**30 + 1, 805306373, 65537, 4099]:
+        vs = {0, 1, 2, 3, p - 1, p - 2, p // 2} | {int(x) for x in rng.integers(0, p, size=300)}
+        cases += [(p, v) for v in sorted(vs)]
+    for p, v in cases:
+        q = oracle.q_of(p)
+        plain = np.full(max(q, 1), 99, dtype=np.int32)
+        fast = np.full(max(q, 1), 99, dtype=np.int32)
+        an = ctypes.c_uint32(0)
+        counts = shim.shim_recv_two_ways(p, v, plain.ctypes.data, fast.ctypes.data, ctypes.byref(an))
+        assert counts == (q | (q << 16)) and an.value == 0, (p, v, counts, an.value)
+        want = oracle.recvschedule(p, v)
+        assert np.array_equal(plain[:q], want) and np.array_equal(fast[:q], want), (p, v)

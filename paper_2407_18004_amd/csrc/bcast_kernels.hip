@@ -156,11 +156,13 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
 // (row within the run << 5 | k) goes into a queue in LDS, and whenever 64 are waiting, and once more at the
 // end of the run, one search per lane fills them in and stores the entries
 // straight into the table.
-constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefront
+constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefront (tables)
+constexpr uint32_t kRowQueueCap = 2u * kWave;         // ... of k_digest: 63 left over + 64 of a tile
+constexpr uint32_t kQueueWords = kDeferCap > kRowQueueCap ? kDeferCap : kRowQueueCap;
 
 // words of LDS per wavefront: slice, receive rows of the tile above, queue
 __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
-  return slice_words(q) + 16u * q + kDeferCap + kRecordWords;
+  return slice_words(q) + 16u * q + kQueueWords + kRecordWords;
 }
 
 __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
   uint32_t *queue = words + slice_w + 16u * q;
-  lockstep_cache_init(record, words + slice_w + 16u * q + kDeferCap);
+  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords);
   const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
@@ -245,33 +247,41 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     if (lane < n_valid)
       open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                 pitch, q, lane, n_valid, n_valid_above);
-    // a queue entry holds the row within the run in 27 bits: runs are far shorter than that,
-    // and a tile beyond it would simply search on the spot
-    const bool can_defer = row0 + kWave - run_row0 <= (1ull << 27);
-    while (__any(open != 0)) {
-      const bool has = open != 0;
-      const uint64_t who = __ballot(has);
-      const uint32_t slot = can_defer ? n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull))
-                                      : kDeferCap;
-      if (has) {
-        const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
-        open &= open - 1u;
-        if (slot < kDeferCap) queue[slot] = ((uint32_t)(row0 + lane - run_row0) << 5) | k;
-        else send_row[k] = (int8_t)search_entry(in, to_processor(in, v, k), k, flags);
-      }
-      if (can_defer) {
+    // Open violations go into the queue as (row within the run) << 5 | k.  A tile can have more
+    // of them than the queue has room for: then the rows leave first, a batch of 64 entries is
+    // filled in (their rows are in the table by then), and the rest is queued after that.
+    const uint32_t rel = (uint32_t)(row0 + lane - run_row0);   // < 2^27: see run_grid
+    bool rows_out = false;
+    for (;;) {
+      while (n_queued < kDeferCap && __any(open != 0)) {
+        const bool has = open != 0;
+        const uint64_t who = __ballot(has);
+        const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
+        if (has && slot < kDeferCap) {
+          const uint32_t k = (uint32_t)(__ffs((int)open) - 1);
+          open &= open - 1u;
+          queue[slot] = (rel << 5) | k;
+        }
         const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
         n_queued = n_new < kDeferCap ? n_new : kDeferCap;
       }
-    }
-    wave_lds_sync();
-    copy_out(row0, n_valid);
-    if (lane < n_valid)
-      for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
-    n_valid_above = n_valid;
-    while (n_queued >= (uint32_t)kWave) {
-      deferred_flush(in, prm, queue, run_row0, n_queued - kWave, n_queued, lane);
-      n_queued -= kWave;
+      wave_lds_sync();
+      if (!rows_out) {
+        copy_out(row0, n_valid);
+        if (lane < n_valid)
+          for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+        n_valid_above = n_valid;
+        rows_out = true;
+      }
+      const bool more = __any(open != 0);
+      while (n_queued >= (uint32_t)kWave || (more && n_queued != 0u)) {
+        const uint32_t n_batch = n_queued < (uint32_t)kWave ? n_queued : (uint32_t)kWave;
+        deferred_flush(in, prm, queue, run_row0, n_queued - n_batch, n_queued, lane);
+        n_queued -= n_batch;
+        if (more) break;                       // room again: queue the rest first
+      }
+      if (!more) break;
+      wave_lds_sync();
     }
     wave_lds_sync();                           // slice and queue are rewritten next
   }
@@ -350,7 +360,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   } else {
     int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
     uint32_t *queue = words + slice_w + 16u * q;
-    lockstep_cache_init(record, words + slice_w + 16u * q + kDeferCap);
+    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords);
     const uint64_t run_row0 = t_lo * kWave;
     uint32_t n_queued = 0;                     // the same in all lanes; at most 63 between tiles
     uint32_t n_valid_above = 0;
@@ -398,11 +408,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         const uint64_t who = __ballot(open != 0);
         const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
         if (open != 0) {
-          if (slot < kDeferCap) queue[slot] = (uint32_t)(row - run_row0);
+          if (slot < kRowQueueCap) queue[slot] = (uint32_t)(row - run_row0);
           else acc_flags |= BCAST_F_SEARCH;    // cannot happen: at most 63 + 64 entries
         }
         const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
-        n_queued = n_new < kDeferCap ? n_new : kDeferCap;
+        n_queued = n_new < kRowQueueCap ? n_new : kRowQueueCap;
         if (lane < n_here)
           for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
         n_valid_above = n_here;
@@ -769,7 +779,9 @@ RunSplit split_runs(uint64_t n_tiles, int grid) {
 // than fit at once even out the load, because a SIMD serves its oldest
 // wavefront first and the young ones of a resident set fall behind by a factor
 // of two.  Measured on MI355X: about six tiles per wavefront is best for long
-// tables, two to four when that would leave fewer than two resident sets.
+// tables, two to four when that would leave fewer than two resident sets.  (A run is never
+// longer than max(6, tiles / 65536) <= 512 tiles, so a row within a run fits 27 bits with room
+// to spare: the queue entries of the kernels rely on that.)
 constexpr uint64_t kRunTiles = 6;
 int run_grid(uint64_t n_tiles, uint32_t resident_per_cu) {
   const int cap = persistent_grid(UINT64_MAX);                  // 64 workgroups per CU

@@ -522,8 +522,15 @@ __global__ void k_u32_zero(uint32_t *x) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *x = 0;
 }
 
+// The ranks of a tile are arbitrary ranks of one instance, so a violation of Algorithm 6 has no
+// neighbour's row to look at: every one takes a search of its own.  Searching where they arise
+// would mean up to four searches in a row with the few lanes that have a first, second, ...
+// violation; instead the tile's violations are collected (owner lane and round, 2 bytes each)
+// and worked off 64 at a time, one per lane.
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
   __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  __shared__ uint16_t open_entry[kWavesPerBlock][4 * kWave];   // lane << 5 | k; at most four per rank
+  __shared__ uint32_t open_v[kWavesPerBlock][kWave];           // the owner's virtual rank
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const uint64_t n_work = (uint64_t)prm.n_inst * prm.tiles_per_inst;
@@ -546,17 +553,45 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     const uint32_t n_valid = prm.m - j0 < (uint32_t)kWave ? prm.m - j0 : (uint32_t)kWave;
     int8_t *recv_row = reinterpret_cast<int8_t *>(lds[wave]) + lane * 2u * q;
     int8_t *send_row = recv_row + q;
+    uint32_t viol = 0;
     if (lane < n_valid) {
       const uint32_t r = prm.ranks[(uint64_t)inst * prm.m + j0 + lane];
-      int b;
       if (r < p) {
-        compute_rank(in, virtual_rank(in, r), recv_row, send_row, b);
+        int b;
+        uint32_t flags;
+        LockstepCache none;
+        lockstep_cache_init(none, nullptr);
+        const uint32_t v = virtual_rank(in, r);
+        open_v[wave][lane] = v;
+        viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags, none, false);
       } else {                           // rank outside the instance: marked row
         for (uint32_t k = 0; k < 2u * q; ++k) recv_row[k] = (int8_t)kInvalidByte;
         if (prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
       }
     }
-    wave_lds_sync();
+    for (;;) {
+      uint32_t n_open = 0;               // the same in all lanes
+      while (n_open + kWave <= 4u * kWave && __any(viol != 0)) {   // one more per lane still fits
+        const bool has = viol != 0;
+        const uint64_t who = __ballot(has);
+        if (has) {
+          const uint32_t slot = n_open + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
+          open_entry[wave][slot] = (uint16_t)((lane << 5) | (uint32_t)(__ffs((int)viol) - 1));
+          viol &= viol - 1u;
+        }
+        n_open += (uint32_t)__popcll(who);
+      }
+      wave_lds_sync();
+      if (n_open == 0) break;
+      for (uint32_t e = lane; e < n_open; e += kWave) {
+        const uint32_t item = open_entry[wave][e];
+        const uint32_t owner = item >> 5, k = item & 31u;
+        uint32_t fl = 0;
+        const int val = search_entry(in, to_processor(in, open_v[wave][owner], k), k, fl);
+        reinterpret_cast<int8_t *>(lds[wave])[owner * 2u * q + q + k] = (int8_t)val;
+      }
+      wave_lds_sync();
+    }
     tile_out<true>(lds[wave], prm.out + off0 + (uint64_t)j0 * 2u * q, n_valid * 2u * q, lane);
     wave_lds_sync();
   }

@@ -183,6 +183,40 @@ def test_long_runs_with_deferred_violations(p, root, a, b):
     assert np.array_equal(want[ranks - a], oracle.schedules_ranks(p, root, ranks.astype(np.uint32), send_mode=0))
 
 
+def test_seeded_long_ranges_at_odd_offsets():
+    # seeded p of every size class, random roots, ranges of 1.2 to 2.6 million ranks that start and
+    # end anywhere (so tiles straddle the root, runs start mid-way through a power of two, and
+    # the records carried from tile to tile see all alignments): table, digest and edge check
+    rng = np.random.default_rng(20240718)
+    for case in range(6):
+        bits = int(rng.integers(22, 32))
+        p = int(rng.integers(2 ** (bits - 1), min(2 ** bits, 2 ** 31 - 1)))
+        if case == 0:
+            p = 2 ** 23 - 1                      # the variant without violations
+        if case == 1:
+            p = 2 ** 24                          # a power of two, root in the middle of the range
+        root = int(rng.integers(0, p))
+        n = int(rng.integers(1_200_000, 2_600_000))
+        n = min(n, p)
+        a = int(rng.integers(0, p - n + 1))
+        if case in (1, 2):                       # put the root inside the range
+            a = max(0, min(p - n, root - n // 3))
+        b = a + n
+        q = lib.bcast_q(p)
+        want = oracle.schedules(p, root=root, r_begin=a, r_end=b, send_mode=1)
+        t = torch.full((n, 2 * q), 99, dtype=torch.int32, device=DEV)
+        lib.bcast_schedules(p, root, a, b, t, t, 2 * q, send_offset=q)
+        torch.cuda.synchronize()
+        got = t.cpu().numpy()
+        del t
+        assert np.array_equal(got, want), (p, root, a, b)
+        assert gpu_digest(p, root, a, b) == oracle.digest(p, root, a, b, send_mode=1), (p, root, a, b)
+        assert gpu_edgecheck(p, root, a, b) == oracle.edgecheck(p, root, a, b, send_mode=1)
+        ranks = np.sort(workloads.streamed_sample_ranks(256, seed=case, p=n).astype(np.int64)) + a
+        assert np.array_equal(want[ranks - a],
+                              oracle.schedules_ranks(p, root, ranks.astype(np.uint32), send_mode=0))
+
+
 def test_argument_errors():
     t = torch.zeros((16, 40), dtype=torch.int32, device=DEV)
     with pytest.raises(lib.BcastError) as e:

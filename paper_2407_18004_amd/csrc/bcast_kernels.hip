@@ -5,8 +5,11 @@
 // a workgroup barrier.  Each lane computes one rank (Algorithms 3, 5, 6) with
 // its state in VGPRs and drops the 2q results as bytes into the wavefront's
 // slice of LDS, laid out exactly like the output rows, so that the tile leaves
-// the CU as 16-byte stores to consecutive addresses.  The grid is a fixed
-// number of workgroups that stride over the tiles.
+// the CU as 16-byte stores to consecutive addresses.  A wavefront works
+// through one contiguous run of tiles and carries what neighbouring tiles have
+// in common from one to the next (LockstepCache); the grid is sized so that
+// runs are a few tiles long and there are several times more workgroups than
+// fit on the chip at once.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -834,9 +837,10 @@ int run_grid(uint64_t n_tiles, uint32_t resident_per_cu) {
 }
 
 // Algorithm 6 has (next to) no violations when every skip below p is a power of
-// two (p = 2^q and p = 2^q - 1): the wavefronts then work alone.  Otherwise the
-// workgroup shares rows and a queue (see tile_rows).  The choice only affects
-// speed: either way a violation that finds no row is resolved by search.
+// two (p = 2^q and p = 2^q - 1): then the few there are are searched for on the
+// spot (tile_rows).  Otherwise the kernels keep the rows of the tile above and
+// defer what those do not answer (k_schedules<true>, k_digest<true, .>).  The
+// choice only affects speed.
 bool keep_next_tile(uint32_t p) { return (p & (p - 1u)) != 0u && (p & (p + 1u)) != 0u; }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

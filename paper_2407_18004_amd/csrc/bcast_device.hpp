@@ -160,7 +160,9 @@ struct TrackOn { static constexpr bool value = true; };
 // How far the difference x - y of a test "x >= y" is from flipping: the test
 // keeps its outcome as long as the difference moves by no more than this.
 __device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
-  const int dxy = (int)(x - y);                 // all operands are below 2^31
+  // operands are below 2^32 and differ by less than 2^32; a difference of 2^31 or more comes
+  // out as a distance of at least 2^29, still far more than any step a record is used across
+  const int dxy = (int)(x - y);
   return (uint32_t)(dxy ^ (dxy >> 31));           // d for d >= 0, -1 - d for d < 0
 }
 
@@ -171,7 +173,7 @@ __device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
 //   Algorithm 6 (kSend): its r' is the same rem, so "lower part" = skip not
 //     taken; e, c and the violation tests as printed, round k = q - j.  While c
 //     still stands for the baseblock, which is not known before the pass ends,
-//     the entries written are placeholders (see leading_rounds).
+//     the entries written are placeholders (see first_level_taken).
 //   Descent of the receive search (see recv_ascent): W = D - 2; a level is
 //     pushed when its skip <= W, accepted for round 0 when skip = W + 1, and the
 //     baseblock's level is not in the list.  A level is the baseblock's exactly
@@ -195,7 +197,8 @@ __device__ __forceinline__ TopDown top_down_start(uint32_t p, uint32_t v) {
   // W = D - 2 as a signed number; after the accept W = -1, which neither fits
   // nor hits any more.  pathr holds the pending calls with level j at bit
   // 31 - j, so that the deepest one is the lowest set bit.  For v >= 2 the first
-  // call (index q, skip p) is always recursive: the walk starts below it.
+  // call (index q, skip p) is always recursive: the walk starts below it (and for
+  // v = 1, W = -1 says that the same index was accepted: see recv_ascent).
   s.W = (int)((is_root ? p : v) - 2u);
   s.pathr = is_root ? 0u : 0x80000000u;
   s.anom = 0;
@@ -203,7 +206,7 @@ __device__ __forceinline__ TopDown top_down_start(uint32_t p, uint32_t v) {
   return s;
 }
 
-//
+// One level of the pass (see TopDown).
 // kTrack: every test whose outcome depends on v also lowers `margin` to its
 // flip distance (tests between constants of the instance are left out; a test
 // that is not consulted may be included, which only makes the margin smaller).

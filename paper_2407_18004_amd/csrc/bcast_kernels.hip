@@ -637,13 +637,13 @@ __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rou
 // then checks that what arrives (its send entry) is for a block it still has.
 template <bool kReverse>
 __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
-  // three [q][kSimBlock] arrays, sized at launch: the lane's recvblock and sendblock and the
-  // sendblock[k] of its from-processor
+  // two [q][kSimBlock] arrays, sized at launch: the lane's recvblock and sendblock.  What the
+  // from-processor sends (its sendblock[k]) is compared with the lane's recvblock[k] once, while
+  // staging; only rounds whose entries differ look it up again (`differs`, bit k).
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   typedef int32_t (*Staged)[kSimBlock];
   Staged st_recv = reinterpret_cast<Staged>(lds_dyn);
   Staged st_send = st_recv + prm.q;
-  Staged st_from = st_send + prm.q;
   const uint32_t lane_b = threadIdx.x;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t root_idx = blockIdx.y;
@@ -660,16 +660,21 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
     const int32_t *own = prm.sched
         ? prm.sched + ((uint64_t)root_idx * p + r_phys) * 2u * q
         : prm.table + (uint64_t)v * 2u * q;
-    for (uint32_t k = 0; k < q; ++k) {
-      st_recv[k][lane_b] = own[k];
-      st_send[k][lane_b] = own[q + k];
+    auto from_entry = [&](uint32_t k) -> int32_t {         // sendblock[k] of the from-processor
       const uint32_t sk = skip_at_level(pm1, q - k);
       const uint32_t f = v >= sk ? v - sk : v + (p - sk);
       const uint32_t f_phys = f + root >= p ? f + root - p : f + root;
       const int32_t *frow = prm.sched
           ? prm.sched + ((uint64_t)root_idx * p + f_phys) * 2u * q
           : prm.table + (uint64_t)f * 2u * q;
-      st_from[k][lane_b] = frow[q + k];
+      return frow[q + k];
+    };
+    uint32_t differs = 0;
+    for (uint32_t k = 0; k < q; ++k) {
+      const int32_t mine = own[k];
+      st_recv[k][lane_b] = mine;
+      st_send[k][lane_b] = own[q + k];
+      differs |= (uint32_t)(from_entry(k) != mine) << k;
     }
     uint32_t *col = prm.possession + (uint64_t)root_idx * prm.n_words * p + v;
     for (uint32_t w = 0; w < prm.n_words; ++w) col[(uint64_t)w * p] = 0u;
@@ -687,15 +692,18 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
       for (uint32_t step = 0; step < prm.rounds; ++step) {
         const uint32_t round = kReverse ? prm.rounds - 1u - step : step;
         int64_t rb = (int64_t)st_recv[k][lane_b] + shift;
-        int64_t fb = (int64_t)st_from[k][lane_b] + shift;
         int64_t sb = (int64_t)st_send[k][lane_b] + shift;
-        const bool has_r = rb >= 0, has_f = fb >= 0;
+        const bool has_r = rb >= 0;
         rb = rb > nm1 ? nm1 : rb;
-        fb = fb > nm1 ? nm1 : fb;
         const uint64_t key = ((uint64_t)round << 32) | r_phys;
-        if (has_r != has_f || (has_r && rb != fb)) {
-          ++n_edge;
-          first_bad = key < first_bad ? key : first_bad;
+        if ((differs >> k) & 1u) {                  // the entries differ: do the blocks?
+          int64_t fb = (int64_t)from_entry(k) + shift;
+          const bool has_f = fb >= 0;
+          fb = fb > nm1 ? nm1 : fb;
+          if (has_r != has_f || (has_r && rb != fb)) {
+            ++n_edge;
+            first_bad = key < first_bad ? key : first_bad;
+          }
         }
         const uint32_t sk = skip_at_level(pm1, q - k);
         const bool to_root = v + sk == p;
@@ -1055,7 +1063,7 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   prm.roots = d_roots; prm.sched = sched; prm.table = table;
   prm.possession = possession; prm.verdict = verdict;
   dim3 grid((p + kSimBlock - 1) / kSimBlock, n_roots);
-  const size_t lds = (size_t)3u * prm.q * kSimBlock * sizeof(int32_t);
+  const size_t lds = (size_t)2u * prm.q * kSimBlock * sizeof(int32_t);
   if (reverse) hipLaunchKernelGGL(k_simulate<true>, grid, dim3(kSimBlock), lds, st, prm);
   else hipLaunchKernelGGL(k_simulate<false>, grid, dim3(kSimBlock), lds, st, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;

@@ -44,6 +44,7 @@ extern "C" {
 #define BCAST_EHIP    (-3)  /* the HIP runtime refused a launch or a copy      */
 
 #define BCAST_MAX_P   2147483647u
+#define BCAST_MAX_N   268435456u   /* blocks in bcast_simulate: 2^28 (the rounds run on 32-bit block numbers) */
 
 /* Flags of bcast_schedules_digest, OR-ed over the ranks (Section 2, the four
  * correctness conditions, and Theorem 3). */
@@ -167,8 +168,8 @@ size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots);
  * rank r for that root), or NULL to have the schedules computed here.
  * workspace: device, at least bcast_simulate_workspace bytes, contents
  * irrelevant on entry.  verdict: device, n_roots structs, overwritten.
- * Errors: domain of p, n = 0, n_roots = 0, a root >= p, NULL pointers,
- * workspace too small (BCAST_ENOMEM). */
+ * Errors: domain of p, n = 0 or n > BCAST_MAX_N, n_roots = 0 or > 65535, a root >= p, NULL
+ * pointers, workspace too small (BCAST_ENOMEM). */
 int bcast_simulate(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
                    const int32_t *sched, void *workspace, size_t workspace_bytes,
                    bcast_verdict *verdict, void *stream);

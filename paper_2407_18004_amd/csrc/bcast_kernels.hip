@@ -635,8 +635,14 @@ __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rou
 // down with all communication reversed.  The bits then mean "partial result
 // already sent on"; a lane first marks the block it sends (its receive entry),
 // then checks that what arrives (its send entry) is for a block it still has.
+//
+// Block numbers fit 32 bits with room to spare (n <= BCAST_MAX_N = 2^28).  Entries, which may be
+// any int32, are clamped to [-C, C], C = n + 2q + 2, while staging: the adjustment
+// q * floor(i / q) - x stays within [-q, n + q], so an entry of C or more is a block >= n - 1 in
+// every round (it counts as n - 1) and one of -C or less is never a block.
 template <bool kReverse>
 __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
+  using Blk = int32_t;
   // two [q][kSimBlock] arrays, sized at launch: the lane's recvblock and sendblock.  What the
   // from-processor sends (its sendblock[k]) is compared with the lane's recvblock[k] once, while
   // staging; only rounds whose entries differ look it up again (`differs`, bit k).
@@ -670,37 +676,41 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
       return frow[q + k];
     };
     uint32_t differs = 0;
+    const int32_t clamp_at = (int32_t)(n + 2u * q + 2u);
+    auto staged = [&](int32_t x) -> int32_t {
+      return x > clamp_at ? clamp_at : (x < -clamp_at ? -clamp_at : x);
+    };
     for (uint32_t k = 0; k < q; ++k) {
       const int32_t mine = own[k];
-      st_recv[k][lane_b] = mine;
-      st_send[k][lane_b] = own[q + k];
+      st_recv[k][lane_b] = staged(mine);
+      st_send[k][lane_b] = staged(own[q + k]);
       differs |= (uint32_t)(from_entry(k) != mine) << k;
     }
     uint32_t *col = prm.possession + (uint64_t)root_idx * prm.n_words * p + v;
     for (uint32_t w = 0; w < prm.n_words; ++w) col[(uint64_t)w * p] = 0u;
 
     if (v != 0) {
-      const int64_t nm1 = (int64_t)n - 1;
+      const Blk nm1 = (Blk)n - 1;
       // round i = x + round uses entry k = i mod q advanced by q * floor(i / q) - x
       const uint32_t i0 = kReverse ? prm.x + prm.rounds - 1u : prm.x;
       uint32_t k = i0 % q;
-      int64_t shift = -(int64_t)prm.x + (int64_t)q * (i0 / q);
+      Blk shift = -(Blk)prm.x + (Blk)q * (Blk)(i0 / q);
       // The word of the possession column that was written last stays in a
       // register: blocks arrive in nearly increasing order, so a word serves
       // some 32 rounds before the next one is fetched.
       uint32_t cw = 0xFFFFFFFFu, cv = 0u;
       for (uint32_t step = 0; step < prm.rounds; ++step) {
         const uint32_t round = kReverse ? prm.rounds - 1u - step : step;
-        int64_t rb = (int64_t)st_recv[k][lane_b] + shift;
-        int64_t sb = (int64_t)st_send[k][lane_b] + shift;
+        Blk rb = (Blk)st_recv[k][lane_b] + shift;
+        Blk sb = (Blk)st_send[k][lane_b] + shift;
         const bool has_r = rb >= 0;
         rb = rb > nm1 ? nm1 : rb;
         const uint64_t key = ((uint64_t)round << 32) | r_phys;
         if ((differs >> k) & 1u) {                  // the entries differ: do the blocks?
-          int64_t fb = (int64_t)from_entry(k) + shift;
+          int64_t fb = (int64_t)from_entry(k) + (int64_t)shift;   // the entry as given, not clamped
           const bool has_f = fb >= 0;
-          fb = fb > nm1 ? nm1 : fb;
-          if (has_r != has_f || (has_r && rb != fb)) {
+          fb = fb > (int64_t)nm1 ? (int64_t)nm1 : fb;
+          if (has_r != has_f || (has_r && (int64_t)rb != fb)) {
             ++n_edge;
             first_bad = key < first_bad ? key : first_bad;
           }
@@ -741,9 +751,9 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
           }
         }
         if (kReverse) {
-          if (k == 0) { k = q - 1u; shift -= q; } else { --k; }
+          if (k == 0) { k = q - 1u; shift -= (Blk)q; } else { --k; }
         } else {
-          if (++k == q) { k = 0; shift += q; }
+          if (++k == q) { k = 0; shift += (Blk)q; }
         }
       }
       if (cw != 0xFFFFFFFFu) col[(uint64_t)cw * p] = cv;
@@ -1013,7 +1023,7 @@ int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *
 // workspace: [roots: n_roots u32][table: p*2q int32][possession: n_roots*n_words*p u32]
 size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots) {
   const int q = host_q(p);
-  if (q < 0 || n == 0 || n_roots == 0) return 0;
+  if (q < 0 || n == 0 || n > BCAST_MAX_N || n_roots == 0) return 0;
   const size_t n_words = ((size_t)n + 31) / 32;
   size_t bytes = align_up((size_t)n_roots * 4, 256);
   bytes += align_up((size_t)p * 2 * (size_t)q * 4, 256);
@@ -1025,7 +1035,7 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
                          uint32_t n_roots, const int32_t *sched, void *workspace,
                          size_t workspace_bytes, bcast_verdict *verdict, void *stream) {
   const int q = host_q(p);
-  if (q < 0 || n == 0 || n > (1u << 30) || n_roots == 0 || n_roots > 65535u || !roots || !verdict)
+  if (q < 0 || n == 0 || n > BCAST_MAX_N || n_roots == 0 || n_roots > 65535u || !roots || !verdict)
     return BCAST_EINVAL;
   for (uint32_t i = 0; i < n_roots; ++i)
     if (roots[i] >= p) return BCAST_EINVAL;

@@ -239,6 +239,10 @@ def test_argument_errors():
     with pytest.raises(lib.BcastError):
         lib.bcast_simulate(100, 10, [100], None, ws, vd)
     assert lib.bcast_simulate_workspace(0, 1, 1) == 0
+    assert lib.bcast_simulate_workspace(100, 2**28 + 1, 1) == 0      # more blocks than BCAST_MAX_N
+    with pytest.raises(lib.BcastError) as e:
+        lib.bcast_simulate(100, 2**28 + 1, [0], None, ws, vd)
+    assert e.value.code == lib.BCAST_EINVAL
     torch.cuda.synchronize()
 
 

@@ -217,6 +217,25 @@ def test_seeded_long_ranges_at_odd_offsets():
                               oracle.schedules_ranks(p, root, ranks.astype(np.uint32), send_mode=0))
 
 
+@pytest.mark.parametrize("p,root,a,n", [
+    (2**31 - 1, 123456789, 123456789 - 1_500_000, 3_000_000),     # the root in the middle of the range
+    (2**31 - 1, 2**31 - 2, 2**31 - 1 - 2_500_000, 2_500_000),     # the last ranks; root = p - 1
+    (2**31 - 1, 1, 0, 2_000_001),                                  # the first ranks; ranks 0, 1, 2 special
+    (2**30, 2**29 + 7, 2**29 - 1_000_000, 2_100_000),             # a power of two
+])
+def test_streamed_ranges_of_the_largest_instances(p, root, a, n):
+    # digests and edge sums of long ranges where wavefronts carry their records across the root
+    b = a + n
+    assert gpu_digest(p, root, a, b) == oracle.digest(p, root, a, b, send_mode=1)
+    assert gpu_edgecheck(p, root, a, b) == oracle.edgecheck(p, root, a, b, send_mode=1)
+    q = lib.bcast_q(p)
+    lo, hi = a + n // 2 - 70_000, a + n // 2 + 70_000             # a table of the middle part
+    t = torch.full((hi - lo, 2 * q), 99, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules(p, root, lo, hi, t, t, 2 * q, send_offset=q)
+    torch.cuda.synchronize()
+    assert np.array_equal(t.cpu().numpy(), oracle.schedules(p, root=root, r_begin=lo, r_end=hi, send_mode=1))
+
+
 def test_argument_errors():
     t = torch.zeros((16, 40), dtype=torch.int32, device=DEV)
     with pytest.raises(lib.BcastError) as e:

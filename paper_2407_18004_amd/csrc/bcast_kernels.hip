@@ -104,6 +104,14 @@ __device__ __forceinline__ void tile_run(const RunSplit &rs, uint64_t &t_lo, uin
   t_hi = lo + rs.base + (w < rs.extra ? 1u : 0u);
 }
 
+// The run of wavefront `wave` of this workgroup: first tile and number of tiles.
+__device__ __forceinline__ void run_of_wave(const RunSplit &rs, uint32_t wave, uint32_t &t_lo,
+                                            uint32_t &n_tiles) {
+  const uint32_t w = blockIdx.x * kWavesPerBlock + wave;
+  t_lo = w * rs.base + (w < rs.extra ? w : rs.extra);
+  n_tiles = rs.base + (w < rs.extra ? 1u : 0u);
+}
+
 // LDS of the tiled kernels is sized at launch: per wavefront one slice of 64
 // rows of 2q bytes (rounded up to 16 bytes).
 __host__ __device__ inline uint32_t slice_words(uint32_t q) { return ((kWave * 2u * q + 15u) / 16u) * 4u; }
@@ -158,7 +166,10 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
 // idle wavefront per tile: the row leaves with the entry still open, its place
 // (row within the run << 5 | k) goes into a queue in LDS, and whenever 64 are waiting, and once more at the
 // end of the run, one search per lane fills them in and stores the entries
-// straight into the table.
+// straight into the table.  At the end of the run the four wavefronts of the
+// workgroup, whose runs are neighbours, meet at a barrier: what the highest tile
+// of a run left open is read from the next wavefront's lowest tile, and the
+// remaining entries of all four are searched for together.
 constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefront (tables)
 constexpr uint32_t kRowQueueCap = 2u * kWave;         // ... of k_digest: 63 left over + 64 of a tile
 constexpr uint32_t kQueueWords = kDeferCap > kRowQueueCap ? kDeferCap : kRowQueueCap;
@@ -288,7 +299,59 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     }
     wave_lds_sync();                           // slice and queue are rewritten next
   }
-  deferred_flush(in, prm, queue, run_row0, 0u, n_queued, lane);
+  // End of the run: fewer than 64 entries are waiting.  The four wavefronts of the workgroup own
+  // neighbouring runs, and each still holds the receive rows of its lowest tile, which is the
+  // tile above the next wavefront's run: after a barrier those rows answer what the first tile
+  // of a run had to leave open, and the rest is pooled so that one search pass serves the
+  // workgroup.  (Every wavefront gets here, also one with an empty run.)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's rows are in the table
+  __syncthreads();
+  const uint32_t wave_words = deferred_wave_words(q);
+  const bool have = lane < n_queued;
+  const uint32_t item = have ? queue[lane] : 0u;
+  bool waiting = have;
+  if (have) {
+    const uint32_t k = item & 31u;
+    const uint64_t row = run_row0 + (item >> 5);
+    const uint64_t target = row + skip_at_level(in.pm1, q - k);          // row of the to-processor
+    for (uint32_t u = wave + 1u; u < (uint32_t)kWavesPerBlock; ++u) {
+      uint32_t u_lo, u_tiles;
+      run_of_wave(prm.runs, u, u_lo, u_tiles);
+      const uint64_t first = (uint64_t)u_lo * kWave;
+      if (u_tiles != 0u && target >= first && target < first + kWave && target < prm.n_ranks) {
+        const int8_t *above_u =
+            reinterpret_cast<const int8_t *>(lds_dyn + u * wave_words + slice_w);
+        prm.send[row * (uint64_t)prm.ld + k] = above_u[(uint32_t)(target - first) * q + k];
+        waiting = false;
+      }
+    }
+  }
+  const uint64_t who = __ballot(waiting);
+  const uint32_t n_left = (uint32_t)__popcll(who);
+  wave_lds_sync();                                   // every lane has read its entry
+  if (waiting) queue[__popcll(who & ((1ull << lane) - 1ull))] = item;
+  if (lane == 0) queue[kQueueWords - 1u] = n_left;   // free: fewer than 64 entries are queued
+  __syncthreads();
+  // entries of the four queues, in the order of the wavefronts: 64 to a wavefront
+  static_assert(kWavesPerBlock == 4, "four queues are pooled");
+  const uint32_t count_at = slice_w + 16u * q + kQueueWords - 1u;
+  const uint32_t end0 = lds_dyn[count_at];
+  const uint32_t end1 = end0 + lds_dyn[wave_words + count_at];
+  const uint32_t end2 = end1 + lds_dyn[2u * wave_words + count_at];
+  const uint32_t end3 = end2 + lds_dyn[3u * wave_words + count_at];
+  const uint32_t mine = wave * kWave + lane;         // all four queues together hold < 256
+  if (mine < end3) {
+    const uint32_t u = (mine >= end0 ? 1u : 0u) + (mine >= end1 ? 1u : 0u) + (mine >= end2 ? 1u : 0u);
+    const uint32_t start = u == 0u ? 0u : u == 1u ? end0 : u == 2u ? end1 : end2;
+    const uint32_t entry = lds_dyn[u * wave_words + slice_w + 16u * q + (mine - start)];
+    uint32_t u_lo, u_tiles;
+    run_of_wave(prm.runs, u, u_lo, u_tiles);
+    const uint64_t row = (uint64_t)u_lo * kWave + (entry >> 5);
+    const uint32_t k = entry & 31u;
+    const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + row));
+    uint32_t fl = 0;
+    prm.send[row * (uint64_t)prm.ld + k] = search_entry(in, to_processor(in, v, k), k, fl);
+  }
 }
 
 // ------------------------------------------------------------------- digest

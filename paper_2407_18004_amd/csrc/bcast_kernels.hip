@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+#include <type_traits>
 
 #include "../../include/bcast.h"
 #include "bcast_device.hpp"
@@ -672,10 +673,26 @@ struct SimParams {
   uint32_t rounds;
   const uint32_t *roots;         // device copy inside the workspace
   const int32_t *sched;          // [n_roots][p][2q] physical, or NULL
-  const int32_t *table;          // [p][2q] by virtual rank (when sched == NULL)
+  const int32_t *table;          // [2q][p]: entry by virtual rank (when sched == NULL)
   uint32_t *possession;          // [n_roots][n_words][p]
   bcast_verdict *verdict;
 };
+
+// [p][c] -> [c][p], 64 rows to a wavefront: the replay reads the table it computes itself by
+// columns, so that the 64 processors of a wavefront read 64 consecutive words.
+__global__ __launch_bounds__(kWave) void k_rows_to_columns(const int32_t *in, int32_t *out,
+                                                           uint32_t p, uint32_t c) {
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  const uint32_t lane = threadIdx.x;
+  const uint64_t row0 = (uint64_t)blockIdx.x * kWave;
+  const uint32_t rows = p - row0 < kWave ? (uint32_t)(p - row0) : kWave;
+  const uint32_t pitch = c | 1u;                              // odd: no bank conflicts by column
+  const int32_t *src = in + row0 * c;
+  for (uint32_t i = lane; i < rows * c; i += kWave) lds_dyn[(i / c) * pitch + i % c] = (uint32_t)src[i];
+  wave_lds_sync();
+  if (lane < rows)
+    for (uint32_t k = 0; k < c; ++k) out[(uint64_t)k * p + row0 + lane] = (int32_t)lds_dyn[lane * pitch + k];
+}
 
 __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rounds) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -703,16 +720,21 @@ __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rou
 // any int32, are clamped to [-C, C], C = n + 2q + 2, while staging: the adjustment
 // q * floor(i / q) - x stays within [-q, n + q], so an entry of C or more is a block >= n - 1 in
 // every round (it counts as n - 1) and one of -C or less is never a block.
-template <bool kReverse>
+//
+// kPacked (C < 2^15, i.e. n below about 32,700): a round's two clamped entries share one LDS word
+// as 16-bit halves: one LDS read per round instead of two, and half the LDS per workgroup, which
+// is what limits the wavefronts per SIMD here.
+template <bool kReverse, bool kPacked>
 __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
   using Blk = int32_t;
-  // two [q][kSimBlock] arrays, sized at launch: the lane's recvblock and sendblock.  What the
-  // from-processor sends (its sendblock[k]) is compared with the lane's recvblock[k] once, while
-  // staging; only rounds whose entries differ look it up again (`differs`, bit k).
+  // two [q][kSimBlock] arrays (one when packed), sized at launch: the lane's recvblock and
+  // sendblock.  What the from-processor sends (its sendblock[k]) is compared with the lane's
+  // recvblock[k] once, while staging; only rounds whose entries differ look it up again
+  // (`differs`, bit k).
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   typedef int32_t (*Staged)[kSimBlock];
   Staged st_recv = reinterpret_cast<Staged>(lds_dyn);
-  Staged st_send = st_recv + prm.q;
+  Staged st_send = st_recv + (kPacked ? 0u : prm.q);
   const uint32_t lane_b = threadIdx.x;
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t root_idx = blockIdx.y;
@@ -723,31 +745,86 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
   const bool active = v < p;
   const uint32_t r_phys = active ? (v + root >= p ? v + root - p : v + root) : 0u;
 
-  uint64_t n_dup = 0, n_unheld = 0, n_edge = 0, n_incomplete = 0, first_bad = UINT64_MAX;
+  // per lane: counts fit 32 bits (at most one of each kind per round, rounds < 2^29), and the
+  // first bad round is kept as a round number; the 64-bit forms are made at the end
+  uint32_t c_dup = 0, c_unheld = 0, c_edge = 0, bad_round = 0xFFFFFFFFu;
+  uint64_t n_incomplete = 0, first_bad = UINT64_MAX;
+
+  const int32_t clamp_at = (int32_t)(n + 2u * q + 2u);
+  auto staged = [&](int32_t x) -> int32_t {
+    return x > clamp_at ? clamp_at : (x < -clamp_at ? -clamp_at : x);
+  };
+  if (prm.sched) {
+    // A caller's table has rows by physical rank.  The workgroup's 128 consecutive virtual ranks
+    // are consecutive physical ranks (starting at the root's offset, wrapping at p), so their
+    // rows form one block of memory (two at the wrap): it is read in memory order, 128
+    // consecutive words at a time, and each word goes to its place [column][processor] in LDS.
+    const uint32_t c = 2u * q;
+    const uint32_t v0 = blockIdx.x * kSimBlock;
+    const uint32_t rows = p - v0 < (uint32_t)kSimBlock ? p - v0 : (uint32_t)kSimBlock;
+    const uint32_t row_step = (uint32_t)kSimBlock / c, col_step = (uint32_t)kSimBlock % c;
+    uint32_t row = lane_b / c, col = lane_b % c;
+    while (row < rows) {
+      const uint32_t u = v0 + row;
+      const uint32_t u_phys = u + root >= p ? u + root - p : u + root;
+      const int32_t val = staged(prm.sched[((uint64_t)root_idx * p + u_phys) * c + col]);
+      if (kPacked) {
+        const uint32_t k = col < q ? col : col - q;
+        reinterpret_cast<uint16_t *>(lds_dyn)[(k * kSimBlock + row) * 2u + (col < q ? 0u : 1u)] =
+            (uint16_t)val;
+      } else {
+        st_recv[col][row] = val;                   // st_send = st_recv + q
+      }
+      row += row_step;
+      col += col_step;
+      if (col >= c) { col -= c; ++row; }
+    }
+    __syncthreads();
+  }
 
   if (active) {
-    const int32_t *own = prm.sched
-        ? prm.sched + ((uint64_t)root_idx * p + r_phys) * 2u * q
-        : prm.table + (uint64_t)v * 2u * q;
+    // entry c (recvblock[c] for c < q, sendblock[c - q] above) of virtual rank u: the table
+    // computed in the call has columns by virtual rank
+    auto entry = [&](uint32_t u, uint32_t c) -> int32_t {
+      if (prm.sched) {
+        const uint32_t u_phys = u + root >= p ? u + root - p : u + root;
+        return prm.sched[((uint64_t)root_idx * p + u_phys) * 2u * q + c];
+      }
+      return prm.table[(uint64_t)c * p + u];
+    };
     auto from_entry = [&](uint32_t k) -> int32_t {         // sendblock[k] of the from-processor
       const uint32_t sk = skip_at_level(pm1, q - k);
-      const uint32_t f = v >= sk ? v - sk : v + (p - sk);
-      const uint32_t f_phys = f + root >= p ? f + root - p : f + root;
-      const int32_t *frow = prm.sched
-          ? prm.sched + ((uint64_t)root_idx * p + f_phys) * 2u * q
-          : prm.table + (uint64_t)f * 2u * q;
-      return frow[q + k];
+      return entry(v >= sk ? v - sk : v + (p - sk), q + k);
     };
+    // `differs` compares clamped entries: two entries that clamp to the same value are equal, or
+    // are both the block n - 1 in every round, or are both never a block
     uint32_t differs = 0;
-    const int32_t clamp_at = (int32_t)(n + 2u * q + 2u);
-    auto staged = [&](int32_t x) -> int32_t {
-      return x > clamp_at ? clamp_at : (x < -clamp_at ? -clamp_at : x);
-    };
     for (uint32_t k = 0; k < q; ++k) {
-      const int32_t mine = own[k];
-      st_recv[k][lane_b] = staged(mine);
-      st_send[k][lane_b] = staged(own[q + k]);
-      differs |= (uint32_t)(from_entry(k) != mine) << k;
+      int32_t mine, out;                           // clamped
+      if (prm.sched) {
+        if (kPacked) {
+          const int32_t both = st_recv[k][lane_b];
+          mine = (int32_t)(int16_t)(both & 0xFFFF);
+          out = both >> 16;
+        } else {
+          mine = st_recv[k][lane_b];
+          out = st_send[k][lane_b];
+        }
+      } else {
+        mine = staged(entry(v, k));
+        out = staged(entry(v, q + k));
+      }
+      // nothing is sent to the root: in the rounds whose to-processor is the root the send
+      // entry is staged as "never a block"
+      const bool to_root = v + skip_at_level(pm1, q - k) == p;
+      out = to_root ? -clamp_at : out;
+      if (kPacked) {
+        st_recv[k][lane_b] = (int32_t)(((uint32_t)mine & 0xFFFFu) | ((uint32_t)out << 16));
+      } else {
+        st_recv[k][lane_b] = mine;
+        st_send[k][lane_b] = out;
+      }
+      differs |= (uint32_t)(staged(from_entry(k)) != mine) << k;
     }
     uint32_t *col = prm.possession + (uint64_t)root_idx * prm.n_words * p + v;
     for (uint32_t w = 0; w < prm.n_words; ++w) col[(uint64_t)w * p] = 0u;
@@ -762,33 +839,38 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
       // register: blocks arrive in nearly increasing order, so a word serves
       // some 32 rounds before the next one is fetched.
       uint32_t cw = 0xFFFFFFFFu, cv = 0u;
-      for (uint32_t step = 0; step < prm.rounds; ++step) {
+      auto note = [&](uint32_t &count, bool bad, uint32_t round) {
+        count += (uint32_t)bad;
+        const uint32_t first = round < bad_round ? round : bad_round;
+        bad_round = bad ? first : bad_round;
+      };
+      // One round.  with_edges: some entry of the from-processors differs from the lane's own,
+      // which never happens on a valid table; then the rounds do not look at `differs` at all.
+      auto one_round = [&](uint32_t step, auto with_edges) {
         const uint32_t round = kReverse ? prm.rounds - 1u - step : step;
-        Blk rb = (Blk)st_recv[k][lane_b] + shift;
-        Blk sb = (Blk)st_send[k][lane_b] + shift;
+        Blk rb, sb;
+        if (kPacked) {
+          const int32_t both = st_recv[k][lane_b];
+          rb = (Blk)(int16_t)(both & 0xFFFF) + shift;
+          sb = (Blk)(both >> 16) + shift;
+        } else {
+          rb = (Blk)st_recv[k][lane_b] + shift;
+          sb = (Blk)st_send[k][lane_b] + shift;
+        }
         const bool has_r = rb >= 0;
         rb = rb > nm1 ? nm1 : rb;
-        const uint64_t key = ((uint64_t)round << 32) | r_phys;
-        if ((differs >> k) & 1u) {                  // the entries differ: do the blocks?
+        if (decltype(with_edges)::value && ((differs >> k) & 1u)) {   // the entries differ: do the blocks?
           int64_t fb = (int64_t)from_entry(k) + (int64_t)shift;   // the entry as given, not clamped
           const bool has_f = fb >= 0;
           fb = fb > (int64_t)nm1 ? (int64_t)nm1 : fb;
-          if (has_r != has_f || (has_r && (int64_t)rb != fb)) {
-            ++n_edge;
-            first_bad = key < first_bad ? key : first_bad;
-          }
+          note(c_edge, has_r != has_f || (has_r && (int64_t)rb != fb), round);
         }
-        const uint32_t sk = skip_at_level(pm1, q - k);
-        const bool to_root = v + sk == p;
-        const bool has_s = sb >= 0 && !to_root;
+        const bool has_s = sb >= 0;
         sb = sb > nm1 ? nm1 : sb;
         if (!kReverse && has_s) {                   // state before this round
           const uint32_t w = (uint32_t)sb >> 5;
           const uint32_t word = w == cw ? cv : col[(uint64_t)w * p];
-          if (((word >> ((uint32_t)sb & 31u)) & 1u) == 0) {
-            ++n_unheld;
-            first_bad = key < first_bad ? key : first_bad;
-          }
+          note(c_unheld, ((word >> ((uint32_t)sb & 31u)) & 1u) == 0u, round);
         }
         if (has_r) {
           const uint32_t w = (uint32_t)rb >> 5;
@@ -798,28 +880,27 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
             cv = col[(uint64_t)w * p];
           }
           const uint32_t bit = 1u << ((uint32_t)rb & 31u);
-          if (cv & bit) {
-            ++n_dup;
-            first_bad = key < first_bad ? key : first_bad;
-          } else {
-            cv |= bit;
-          }
+          note(c_dup, (cv & bit) != 0u, round);
+          cv |= bit;
         }
         if (kReverse && has_s) {                    // state after this round's send
           const uint32_t w = (uint32_t)sb >> 5;
           const uint32_t word = w == cw ? cv : col[(uint64_t)w * p];
-          if (((word >> ((uint32_t)sb & 31u)) & 1u) != 0) {
-            ++n_unheld;
-            first_bad = key < first_bad ? key : first_bad;
-          }
+          note(c_unheld, ((word >> ((uint32_t)sb & 31u)) & 1u) != 0u, round);
         }
         if (kReverse) {
           if (k == 0) { k = q - 1u; shift -= (Blk)q; } else { --k; }
         } else {
           if (++k == q) { k = 0; shift += (Blk)q; }
         }
+      };
+      if (__any(differs != 0u)) {
+        for (uint32_t step = 0; step < prm.rounds; ++step) one_round(step, std::true_type{});
+      } else {
+        for (uint32_t step = 0; step < prm.rounds; ++step) one_round(step, std::false_type{});
       }
       if (cw != 0xFFFFFFFFu) col[(uint64_t)cw * p] = cv;
+      if (bad_round != 0xFFFFFFFFu) first_bad = ((uint64_t)bad_round << 32) | r_phys;
       uint32_t have = 0;
       for (uint32_t w = 0; w < prm.n_words; ++w) {
         uint32_t word = col[(uint64_t)w * p];
@@ -833,6 +914,7 @@ __global__ __launch_bounds__(kSimBlock) void k_simulate(SimParams prm) {
       }
     }
   }
+  uint64_t n_dup = c_dup, n_unheld = c_unheld, n_edge = c_edge;
 
   // wavefront reductions, then one atomic per counter that is not zero
   const uint64_t bad_lanes = __ballot(n_incomplete != 0);
@@ -1083,13 +1165,14 @@ int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 
-// workspace: [roots: n_roots u32][table: p*2q int32][possession: n_roots*n_words*p u32]
+// workspace: [roots: n_roots u32][table by rows: p*2q int32][the same by columns]
+//            [possession: n_roots*n_words*p u32]
 size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots) {
   const int q = host_q(p);
   if (q < 0 || n == 0 || n > BCAST_MAX_N || n_roots == 0) return 0;
   const size_t n_words = ((size_t)n + 31) / 32;
   size_t bytes = align_up((size_t)n_roots * 4, 256);
-  bytes += align_up((size_t)p * 2 * (size_t)q * 4, 256);
+  bytes += 2u * align_up((size_t)p * 2 * (size_t)q * 4, 256);
   bytes += align_up((size_t)n_roots * n_words * p * 4, 256);
   return bytes + 256;
 }
@@ -1117,6 +1200,8 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   base += align_up((size_t)n_roots * 4, 256);
   int32_t *table = reinterpret_cast<int32_t *>(base);
   base += align_up((size_t)p * 2 * (size_t)q * 4, 256);
+  int32_t *columns = reinterpret_cast<int32_t *>(base);
+  base += align_up((size_t)p * 2 * (size_t)q * 4, 256);
   uint32_t *possession = reinterpret_cast<uint32_t *>(base);
 
   // The roots array is small; it is copied through the stream so that the
@@ -1128,17 +1213,28 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   if (!sched) {
     const int rc = bcast_schedules(p, 0, 0, p, table, table + q, 2 * (int64_t)q, stream);
     if (rc != BCAST_OK) return rc;
+    const uint32_t c = 2u * (uint32_t)q;
+    hipLaunchKernelGGL(k_rows_to_columns, dim3((p + kWave - 1) / kWave), dim3(kWave),
+                       (size_t)kWave * (c | 1u) * 4u, st, table, columns, p, c);
+    if (!launch_ok()) return BCAST_EHIP;
   }
   SimParams prm;
   prm.p = p; prm.q = (uint32_t)q; prm.n = n; prm.n_words = (n + 31u) / 32u;
   prm.x = ((uint32_t)q - (n - 1u) % (uint32_t)q) % (uint32_t)q;
   prm.rounds = rounds;
-  prm.roots = d_roots; prm.sched = sched; prm.table = table;
+  prm.roots = d_roots; prm.sched = sched; prm.table = columns;
   prm.possession = possession; prm.verdict = verdict;
   dim3 grid((p + kSimBlock - 1) / kSimBlock, n_roots);
-  const size_t lds = (size_t)2u * prm.q * kSimBlock * sizeof(int32_t);
-  if (reverse) hipLaunchKernelGGL(k_simulate<true>, grid, dim3(kSimBlock), lds, st, prm);
-  else hipLaunchKernelGGL(k_simulate<false>, grid, dim3(kSimBlock), lds, st, prm);
+  // clamped entries lie in [-C, C], C = n + 2q + 2: as 16-bit halves of one word when that fits
+  const bool packed = (uint64_t)n + 2u * prm.q + 2u <= 32767u;
+  const size_t lds = (size_t)(packed ? 1u : 2u) * prm.q * kSimBlock * sizeof(int32_t);
+  if (reverse) {
+    if (packed) hipLaunchKernelGGL((k_simulate<true, true>), grid, dim3(kSimBlock), lds, st, prm);
+    else hipLaunchKernelGGL((k_simulate<true, false>), grid, dim3(kSimBlock), lds, st, prm);
+  } else {
+    if (packed) hipLaunchKernelGGL((k_simulate<false, true>), grid, dim3(kSimBlock), lds, st, prm);
+    else hipLaunchKernelGGL((k_simulate<false, false>), grid, dim3(kSimBlock), lds, st, prm);
+  }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 

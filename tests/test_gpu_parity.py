@@ -470,6 +470,33 @@ def test_simulation_block_counts(p, n):
     assert gpu_simulate(p, n, [root])[0] == oracle.simulate(p, n, root)
 
 
+@pytest.mark.parametrize("p,n", [
+    (1000, 32745), (1000, 32746),      # the last n whose entries are staged as 16-bit halves, and the first beyond
+    (100, 40000), (17, 100003),
+])
+def test_simulation_many_blocks(p, n):
+    # both ways of staging the entries, with planted mistakes and entries far out of range
+    q = oracle.q_of(p)
+    root = p // 3
+    assert gpu_simulate(p, n, [root])[0] == oracle.simulate(p, n, root)
+    assert gpu_simulate(p, n, [root], reduce=True)[0] == oracle.simulate_reduce(p, n, root)
+    rng = np.random.default_rng(p + n)
+    tab = oracle.schedules(p, root=root)
+    for _ in range(4):
+        r, c = int(rng.integers(0, p)), int(rng.integers(0, 2 * q))
+        tab[r, c] = int(rng.integers(-q, q))
+    tab[5, 1] = 2**31 - 1
+    tab[6, q + 1] = -(2**31)
+    tab[7, 0] = n + 2 * q + 2           # exactly the clamping bound, and one off on either side
+    tab[8, q] = n + 2 * q + 1
+    tab[9, 2] = -(n + 2 * q + 3)
+    sched = torch.from_numpy(tab[None]).to(DEV)
+    want = oracle.simulate(p, n, root, tab)
+    assert want["flags"] != 0
+    assert gpu_simulate(p, n, [root], sched)[0] == want
+    assert gpu_simulate(p, n, [root], sched, reduce=True)[0] == oracle.simulate_reduce(p, n, root, tab)
+
+
 # ------------------------------------------------ reduction by reversal ----
 
 @pytest.mark.parametrize("p", [1, 2, 3, 17, 100, 1000, 4096, 65537])

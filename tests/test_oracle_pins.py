@@ -173,6 +173,22 @@ def test_conditions_small_p_both_send_routes():
         check_conditions(p, oracle.schedules(p, send_mode=0))
 
 
+def test_lemma5_receive_index_is_a_baseblock_of_its_interval():
+    # Lemma 5: the skip index found for round k is the baseblock of some processor r' with
+    # r - skip[k+1] <= r' <= r - skip[k] (taken on p + r, i.e. modulo p), checked against a
+    # listing of all baseblocks.  The index is q exactly where the entry is not negative.
+    for p in list(range(2, 260)) + [511, 512, 513, 1000, 1025]:
+        q = oracle.q_of(p)
+        sk = oracle.skips(p)
+        recv = oracle.schedules(p, send_mode=1)[:, :q]
+        bb = np.array([oracle.baseblock(p, r) for r in range(p)])
+        for r in range(p):
+            for k in range(q):
+                idx = q if recv[r, k] >= 0 else recv[r, k] + q
+                window = np.arange(p + r - sk[k + 1], p + r - sk[k] + 1) % p
+                assert (bb[window] == idx).any(), (p, r, k)
+
+
 def test_algorithm6_equals_definition_exhaustive():
     # Algorithm 6 must reach exactly the definition (Condition 2) for every rank.
     for p in range(1, P_EXHAUSTIVE + 1):

@@ -12,14 +12,17 @@
  * one GPU lane per rank.
  *
  * Conventions for every entry point
- *  - "host" pointers are dereferenced by the calling thread; "device" pointers
- *    are only passed to kernels.  The caller owns every buffer and the stream;
- *    the library allocates nothing and keeps no state between calls.
+ *  - "host" pointers are dereferenced by the calling thread, before the call
+ *    returns; "device" pointers are only passed to kernels.  The caller owns
+ *    every buffer and the stream; the library allocates nothing and keeps no
+ *    state between calls.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued on it and the call returns without waiting; results are
  *    valid once the caller has synchronised the stream.
  *  - Return value: BCAST_OK, or a negative BCAST_E* code.  Nothing is thrown
- *    and nothing aborts.  On an error no kernel has been launched.
+ *    and nothing aborts.  Arguments are checked before anything is launched:
+ *    on BCAST_EINVAL and BCAST_ENOMEM no kernel has run.  BCAST_EHIP means the
+ *    HIP runtime refused a launch; kernels launched before it may have run.
  *  - Domain: 1 <= p <= 2^31 - 1, so q <= 31.  p = 1 has q = 0: rows are empty.
  *  - Schedule entries are the raw values of Algorithms 5 and 6, in [-q, q-1]:
  *    exactly one receive entry of a non-root rank is non-negative (its
@@ -137,9 +140,11 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin,
  * overlapping tables. */
 int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *stream);
 
-/* Many instances at once: instance i has p[i] processors, root[i], and asks for
- * the m physical ranks ranks[i*m .. i*m+m).  Row j of instance i, 2*q(p[i])
- * int32 {recv[0..q-1], send[0..q-1]}, is written at
+/* Algorithms 3, 5 (with 4) and 6 for listed ranks of many instances at once (the
+ * skips of Algorithm 2 per instance): instance i has p[i] processors, root[i]
+ * (renumbering as in Section 2), and asks for the m physical ranks
+ * ranks[i*m .. i*m+m).  Row j of instance i, 2*q(p[i]) int32
+ * {recvblock[0..q-1], sendblock[0..q-1]} of that rank, is written at
  *     out[row_off[i] + j * 2*q(p[i])].
  * p, root, ranks, row_off (n_inst+1 prefix sums, in int32 elements) and out are
  * device arrays; out holds out_elems elements.  Nothing can be validated on
@@ -153,7 +158,12 @@ int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *
                             const uint64_t *row_off, int32_t *out,
                             uint64_t out_elems, uint32_t *n_rejected, void *stream);
 
-/* Bytes of device workspace bcast_simulate needs (0 on invalid arguments). */
+/* Bytes of device workspace bcast_simulate and bcast_simulate_reduce need for
+ * the replay of Algorithm 1 with n blocks from n_roots roots on p processors:
+ * the roots, the schedule table of Algorithms 5 and 6 twice (by rows and by
+ * columns, 8q bytes per processor each) and one possession bit per root,
+ * processor and block.  0 when an argument is outside the domain documented at
+ * bcast_simulate or the size does not fit size_t. */
 size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots);
 
 /* Algorithm 1 (and, for several roots side by side, Algorithm 7) replayed over

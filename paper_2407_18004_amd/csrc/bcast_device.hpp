@@ -478,7 +478,8 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
           j0 == cache.mem[kRecJ]) {
         const uint32_t dD = D - cache.D, dM = M - cache.M;
         const uint32_t far = flip_distance(D, cache.D) + flip_distance(M, cache.M) + 2u;
-        const bool ok = dD == lane0_of(dD) && dM == lane0_of(dM) && far <= cache.mem[kRecMargin] &&
+        const uint32_t dD0 = lane0_of(dD), dM0 = lane0_of(dM);   // read by all lanes, whatever the tests say
+        const bool ok = dD == dD0 && dM == dM0 && far <= cache.mem[kRecMargin] &&
                         it + cache.mem[kRecIters] <= cap;
         if (!__any(!ok)) {
           for (uint32_t kk = k0; kk < q; ++kk) {
@@ -541,7 +542,8 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   const uint32_t n_top = use ? top_level_count(in.pm1, q) : 0u;
   if (n_top >= 4u) {
     const uint32_t dv = v - cache.top_v;
-    const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == lane0_of(dv) &&
+    const uint32_t dv0 = lane0_of(dv);
+    const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == dv0 &&
                       flip_distance(v, cache.top_v) + 1u <= cache.mem[kTopMargin];
     if (!__any(!near)) {
       s.rem = v - cache.mem[kTopT];
@@ -556,17 +558,19 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       for (; j <= n_top; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
       const uint32_t T = v - s.rem, Tw = v - (uint32_t)s.W;
       const uint32_t bits = (uint32_t)s.closed | (s.anom << 1);
-      const bool same = T == lane0_of(T) && Tw == lane0_of(Tw) && s.jb == lane0_of(s.jb) &&
-                        s.pathr == lane0_of(s.pathr) && s.e == lane0_of(s.e) &&
-                        (uint32_t)s.c == lane0_of((uint32_t)s.c) && s.viol == lane0_of(s.viol) &&
-                        bits == lane0_of(bits);
+      // lane 0's values, read by all lanes before any of them is compared
+      const uint32_t T0 = lane0_of(T), Tw0 = lane0_of(Tw), jb0 = lane0_of(s.jb), pathr0 = lane0_of(s.pathr),
+                     e0 = lane0_of(s.e), c0 = lane0_of((uint32_t)s.c), viol0 = lane0_of(s.viol),
+                     bits0 = lane0_of(bits);
+      const bool same = T == T0 && Tw == Tw0 && s.jb == jb0 && s.pathr == pathr0 && s.e == e0 &&
+                        (uint32_t)s.c == c0 && s.viol == viol0 && bits == bits0;
       cache.mem[kTopValid] = (uint32_t)!__any(!same);
       cache.mem[kTopLevels] = n_top;
       cache.top_v = v;
-      cache.mem[kTopT] = lane0_of(T); cache.mem[kTopTw] = lane0_of(Tw); cache.mem[kTopJb] = lane0_of(s.jb);
-      cache.mem[kTopPathr] = lane0_of(s.pathr); cache.mem[kTopE] = lane0_of(s.e);
-      cache.mem[kTopC] = lane0_of((uint32_t)s.c); cache.mem[kTopViol] = lane0_of(s.viol);
-      cache.mem[kTopBits] = lane0_of(bits);
+      cache.mem[kTopT] = T0; cache.mem[kTopTw] = Tw0; cache.mem[kTopJb] = jb0;
+      cache.mem[kTopPathr] = pathr0; cache.mem[kTopE] = e0;
+      cache.mem[kTopC] = c0; cache.mem[kTopViol] = viol0;
+      cache.mem[kTopBits] = bits0;
       cache.mem[kTopMargin] = wave_min32(margin);
     }
     j = n_top + 1u;

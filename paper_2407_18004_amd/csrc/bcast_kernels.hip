@@ -704,6 +704,18 @@ __global__ __launch_bounds__(kWave) void k_rows_to_columns(const int32_t *in, in
     for (uint32_t k = 0; k < c; ++k) out[(uint64_t)k * p + row0 + lane] = (int32_t)lds_dyn[lane * pitch + k];
 }
 
+// The roots reach the device as kernel arguments, kRootBatch at a time: no copy from the
+// caller's host array is left pending when the call returns, and nothing waits.
+constexpr uint32_t kRootBatch = 256;
+struct RootBatch {
+  uint32_t first, count;
+  uint32_t root[kRootBatch];
+};
+
+__global__ __launch_bounds__(kRootBatch) void k_store_roots(uint32_t *dst, RootBatch b) {
+  if (threadIdx.x < b.count) dst[b.first + threadIdx.x] = b.root[threadIdx.x];
+}
+
 __global__ void k_verdict_init(bcast_verdict *vd, uint32_t n_roots, uint32_t rounds) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n_roots) {
@@ -956,20 +968,15 @@ int host_q(uint32_t p) {
 }
 
 int persistent_grid(uint64_t n_blocks_wanted) {
-  static int cus[64] = {0};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return -1;
-  if (cus[dev] == 0) {
-    int n = 0;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      return -1;
-    cus[dev] = n;
-  }
+  int dev = 0, n_cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -1;
+  if (hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cus <= 0)
+    return -1;
   // Many more workgroups than fit at once: ranks take different numbers of
   // steps, and the dispatcher evens that out by handing out the next workgroup
   // whenever one ends.  64 per CU measured best on MI355X (8: 19 % slower;
   // one tile per wavefront: one atomic per wavefront on one address, 2x slower).
-  const uint64_t cap = (uint64_t)cus[dev] * 64u;
+  const uint64_t cap = (uint64_t)n_cus * 64u;
   const uint64_t g = n_blocks_wanted < cap ? n_blocks_wanted : cap;
   return (int)(g == 0 ? 1 : g);
 }
@@ -1211,14 +1218,19 @@ int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *
 
 // workspace: [roots: n_roots u32][table by rows: p*2q int32][the same by columns]
 //            [possession: n_roots*n_words*p u32]
+// 0 when the arguments are outside the domain or the size does not fit size_t.
 size_t bcast_simulate_workspace(uint32_t p, uint32_t n, uint32_t n_roots) {
   const int q = host_q(p);
-  if (q < 0 || n == 0 || n > BCAST_MAX_N || n_roots == 0) return 0;
-  const size_t n_words = ((size_t)n + 31) / 32;
-  size_t bytes = align_up((size_t)n_roots * 4, 256);
-  bytes += 2u * align_up((size_t)p * 2 * (size_t)q * 4, 256);
-  bytes += align_up((size_t)n_roots * n_words * p * 4, 256);
-  return bytes + 256;
+  if (q < 0 || n == 0 || n > BCAST_MAX_N || n_roots == 0 || n_roots > 65535u) return 0;
+  const unsigned __int128 n_words = ((uint64_t)n + 31u) / 32u;
+  const unsigned __int128 limit = (unsigned __int128)SIZE_MAX - 4096u;
+  unsigned __int128 bytes = align_up((size_t)n_roots * 4, 256);
+  bytes += 2u * (unsigned __int128)align_up((size_t)p * 2 * (size_t)q * 4, 256);   // < 2^40
+  const unsigned __int128 possession = (unsigned __int128)n_roots * n_words * p * 4u;   // < 2^16 2^23 2^31 4
+  if (possession > limit) return 0;
+  bytes += (possession + 255u) / 256u * 256u;
+  bytes += 256u;
+  return bytes > limit ? 0 : (size_t)bytes;
 }
 
 static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *roots,
@@ -1230,8 +1242,10 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   for (uint32_t i = 0; i < n_roots; ++i)
     if (roots[i] >= p) return BCAST_EINVAL;
   const size_t need = bcast_simulate_workspace(p, n, n_roots);
-  if (!workspace) return BCAST_EINVAL;
+  if (!workspace || need == 0) return BCAST_EINVAL;
   if (workspace_bytes < need) return BCAST_ENOMEM;
+  // the last thing that can fail before a launch: asking the device for its size
+  if (persistent_grid(1) < 0) return BCAST_EHIP;
   hipStream_t st = (hipStream_t)stream;
   const uint32_t rounds = q == 0 ? 0u : n - 1u + (uint32_t)q;
   hipLaunchKernelGGL(k_verdict_init, dim3((n_roots + 63) / 64), dim3(64), 0, st, verdict,
@@ -1248,11 +1262,15 @@ static int simulate_impl(bool reverse, uint32_t p, uint32_t n, const uint32_t *r
   base += align_up((size_t)p * 2 * (size_t)q * 4, 256);
   uint32_t *possession = reinterpret_cast<uint32_t *>(base);
 
-  // The roots array is small; it is copied through the stream so that the
-  // caller's host array may be reused as soon as the call returns.
-  if (hipMemcpyAsync(d_roots, roots, (size_t)n_roots * 4, hipMemcpyHostToDevice, st) != hipSuccess)
-    return BCAST_EHIP;
-  if (hipStreamSynchronize(st) != hipSuccess) return BCAST_EHIP;
+  for (uint32_t first = 0; first < n_roots; first += kRootBatch) {
+    RootBatch b;
+    b.first = first;
+    b.count = n_roots - first < kRootBatch ? n_roots - first : kRootBatch;
+    memcpy(b.root, roots + first, (size_t)b.count * 4);
+    if (b.count < kRootBatch) memset(b.root + b.count, 0, (size_t)(kRootBatch - b.count) * 4);
+    hipLaunchKernelGGL(k_store_roots, dim3(1), dim3(kRootBatch), 0, st, d_roots, b);
+    if (!launch_ok()) return BCAST_EHIP;
+  }
 
   if (!sched) {
     const int rc = bcast_schedules(p, 0, 0, p, table, table + q, 2 * (int64_t)q, stream);

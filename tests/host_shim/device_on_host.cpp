@@ -3,11 +3,108 @@
 // without a GPU, under gdb or a sanitizer if need be.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
+#include <ucontext.h>
+
+#include <functional>
 
 #include "../../paper_2407_18004_amd/csrc/bcast_device.hpp"
 
 using namespace bcast;
+
+// A wavefront on the CPU: every lane is a coroutine with a stack of its own.  A lane runs until
+// it reaches a cross-lane operation and waits there; once every lane that has not finished is
+// waiting, the operation is carried out over the waiting lanes (the active lanes of the GPU)
+// and they go on.  Lanes that meet must have reached the same operation at the same place in
+// the source and as their n-th operation, which holds for code whose cross-lane operations sit
+// in control flow that is the same for all lanes; anything else is counted in `mismatches`.
+namespace shim_wave {
+
+constexpr int kLanes = 64;
+constexpr size_t kStackBytes = 256 * 1024;
+
+struct Lane {
+  ucontext_t ctx;
+  bool done, waiting;
+  int op, value, arg, site, result;
+  uint64_t n_ops;
+};
+
+static Lane lanes[kLanes];
+static char *stacks = nullptr;
+static ucontext_t scheduler;
+static int current = -1;                     // lane that is running, -1 outside run()
+static const std::function<void(int)> *body = nullptr;
+static uint64_t mismatches = 0, operations = 0;
+
+int cross_lane(Op op, int value, int arg, int site) {
+  if (current < 0) return value;             // a wavefront of one lane
+  Lane &l = lanes[current];
+  l.op = op; l.value = value; l.arg = arg; l.site = site;
+  l.waiting = true;
+  ++l.n_ops;
+  swapcontext(&l.ctx, &scheduler);
+  return l.result;
+}
+
+static void lane_main() {
+  (*body)(current);
+  lanes[current].done = true;
+  swapcontext(&lanes[current].ctx, &scheduler);
+}
+
+void run(int n_lanes, const std::function<void(int)> &f) {
+  if (!stacks) stacks = (char *)malloc(kLanes * kStackBytes);
+  body = &f;
+  for (int l = 0; l < n_lanes; ++l) {
+    Lane &ln = lanes[l];
+    getcontext(&ln.ctx);
+    ln.ctx.uc_stack.ss_sp = stacks + (size_t)l * kStackBytes;
+    ln.ctx.uc_stack.ss_size = kStackBytes;
+    ln.ctx.uc_link = &scheduler;
+    makecontext(&ln.ctx, lane_main, 0);
+    ln.done = false; ln.waiting = false; ln.n_ops = 0;
+  }
+  for (;;) {
+    for (int l = 0; l < n_lanes; ++l) {
+      if (lanes[l].done || lanes[l].waiting) continue;
+      current = l;
+      swapcontext(&scheduler, &lanes[l].ctx);
+    }
+    current = -1;
+    int first = -1;
+    for (int l = 0; l < n_lanes; ++l)
+      if (!lanes[l].done) { first = l; break; }
+    if (first < 0) break;
+    // every lane still alive is waiting: carry out the operation over them
+    const Lane &f0 = lanes[first];
+    int any = 0;
+    for (int l = 0; l < n_lanes; ++l) {
+      if (lanes[l].done) continue;
+      if (lanes[l].op != f0.op || lanes[l].site != f0.site || lanes[l].n_ops != f0.n_ops ||
+          (f0.op == kShflXor && lanes[l].arg != f0.arg))
+      { if (!mismatches && getenv("SHIM_WAVE_DEBUG")) fprintf(stderr, "mismatch: lane %d op %d site %d n %llu vs lane %d op %d site %d n %llu\n", l, lanes[l].op, lanes[l].site, (unsigned long long)lanes[l].n_ops, first, f0.op, f0.site, (unsigned long long)f0.n_ops); ++mismatches; }
+      any |= lanes[l].value;
+    }
+    ++operations;
+    for (int l = 0; l < n_lanes; ++l) {
+      Lane &ln = lanes[l];
+      if (ln.done) continue;
+      if (ln.op == kAny) ln.result = any;
+      else if (ln.op == kFirstLane) ln.result = f0.value;
+      else {                                   // the partner's value; an idle partner gives one's own
+        const int partner = l ^ ln.arg;
+        ln.result = partner < n_lanes && !lanes[partner].done ? lanes[partner].value : ln.value;
+      }
+    }
+    for (int l = 0; l < n_lanes; ++l) lanes[l].waiting = false;
+  }
+  body = nullptr;
+}
+
+}  // namespace shim_wave
 
 static uint32_t q_of(uint32_t p) {
   uint32_t q = 0;
@@ -19,7 +116,7 @@ static uint64_t g_replays = 0, g_top_replays = 0;
 
 extern "C" {
 
-// searches of the last shim_schedules_tiles call that replayed a lockstep record
+// tiles of the last shim_schedules_tiles call that replayed a lockstep record
 uint64_t shim_last_replays(void) { return g_replays; }
 // ... and that took over the state after the top levels
 uint64_t shim_last_top_replays(void) { return g_top_replays; }
@@ -46,66 +143,86 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
   return (int)q;
 }
 
-// The same for n consecutive physical ranks from r_begin, in tiles of 64 lanes
-// the way a wavefront works through them: phase one for every lane, then
-// violations filled in from rows of the same tile, then the rest by search.
+// The same for n consecutive physical ranks from r_begin, the way the wavefronts of the kernels
+// work through them: the tiles of 64 ranks are dealt out as runs of run_tiles tiles (0: one run),
+// one wavefront to a run with a fresh record; inside a run the tiles are taken from the highest
+// down with the receive rows of the tile above at hand (descending != 0: the kernels for p with
+// violations of Algorithm 6) or from the lowest up without them (the kernels for p = 2^q and
+// 2^q - 1).  Phase one of a tile runs as a wavefront of 64 lanes (shim_wave::run) with one
+// record shared by the lanes, as in LDS; then violations are filled in from rows of the same
+// tile or the tile above, then the rest by search.
 int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n,
+                         uint32_t run_tiles, int descending,
                          int32_t *rows, uint32_t *flags_out, uint64_t *hash_out,
                          uint64_t *n_from_tile) {
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
   uint64_t borrowed = 0;
-  // tiles from the highest down, as a wavefront does within its run: one slice that is reused
-  // (rows of the previous tile stay where they are until they are overwritten) and a copy of the
-  // receive rows of the tile above
+  // one slice that is reused (rows of the previous tile stay where they are until they are
+  // overwritten) and a copy of the receive rows of the tile above
   static int8_t tile[64 * 62];
   static int8_t above[64 * 31];
-  memset(tile, 0x55, sizeof tile);
-  // one record per lane position: lane l sees ranks 64 apart, as on the GPU
-  static LockstepCache caches[64];
-  static uint32_t record_mem[64][kRecordWords];
-  for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem[l]);
-  uint32_t n_valid_next = 0;
-  const int8_t *next_recv = nullptr;
-  const uint64_t n_tiles = (n + 63) / 64;
-  for (uint64_t ti = n_tiles; ti-- > 0;) {
-    const uint64_t row0 = ti * 64;
-    const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
-    uint32_t viol[64], fl[64], vr[64];
-    int b[64];
-    for (uint32_t lane = 0; lane < n_valid; ++lane) {
-      vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
-      viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
-                                       tile + lane * 2 * q + q, b[lane], fl[lane],
-                                       caches[lane], n_valid == 64);
-    }
-    for (uint32_t lane = 0; lane < n_valid; ++lane) {
-      int8_t *recv_row = tile + lane * 2 * q;
-      const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
-                                               2 * q, q, lane, n_valid, n_valid_next);
-      borrowed += (uint64_t)__popc(viol[lane] ^ open);
-      fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
-    }
-    for (uint32_t lane = 0; lane < n_valid; ++lane) {
-      const uint64_t i = row0 + lane;
-      const int8_t *recv_row = tile + lane * 2 * q;
-      for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = recv_row[k];
-      uint64_t h = 0;
-      uint32_t fl2 = 0;
-      digest_rank(in, (uint32_t)(r_begin + i), vr[lane], b[lane], recv_row, h, fl2);
-      if (flags_out) flags_out[i] = fl[lane] | fl2;
-      if (hash_out) hash_out[i] = h;
-      for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
-    }
-    next_recv = above;
-    n_valid_next = n_valid;
-  }
-  if (n_from_tile) *n_from_tile = borrowed;
+  static LockstepCache caches[64];            // D, M, top_v are per lane ...
+  static uint32_t record_mem[kRecordWords];   // ... the rest is the wavefront's
   g_replays = 0;
   g_top_replays = 0;
-  for (int l = 0; l < 64; ++l) { g_replays += caches[l].mem[kRecReplays]; g_top_replays += caches[l].mem[kTopReplays]; }
+  shim_wave::mismatches = 0;
+  shim_wave::operations = 0;
+  const uint64_t n_tiles = (n + 63) / 64;
+  const uint64_t per_run = run_tiles ? run_tiles : (n_tiles ? n_tiles : 1);
+  for (uint64_t run0 = 0; run0 < n_tiles; run0 += per_run) {
+    const uint64_t run1 = run0 + per_run < n_tiles ? run0 + per_run : n_tiles;
+    memset(tile, 0x55, sizeof tile);
+    for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem);
+    const bool long_run = run1 - run0 >= 3;   // as in the kernels
+    uint32_t n_valid_next = 0;
+    const int8_t *next_recv = nullptr;
+    for (uint64_t step = 0; step < run1 - run0; ++step) {
+      const uint64_t ti = descending ? run1 - 1 - step : run0 + step;
+      const uint64_t row0 = ti * 64;
+      const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
+      uint32_t viol[64], fl[64], vr[64];
+      int b[64];
+      shim_wave::run((int)n_valid, [&](int lane) {
+        vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
+        viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
+                                         tile + lane * 2 * q + q, b[lane], fl[lane],
+                                         caches[lane], long_run && n_valid == 64);
+      });
+      for (uint32_t lane = 0; lane < n_valid; ++lane) {
+        int8_t *recv_row = tile + lane * 2 * q;
+        const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
+                                                 2 * q, q, lane, n_valid, n_valid_next);
+        borrowed += (uint64_t)__popc(viol[lane] ^ open);
+        fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
+      }
+      for (uint32_t lane = 0; lane < n_valid; ++lane) {
+        const uint64_t i = row0 + lane;
+        const int8_t *recv_row = tile + lane * 2 * q;
+        for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = recv_row[k];
+        uint64_t h = 0;
+        uint32_t fl2 = 0;
+        digest_rank(in, (uint32_t)(r_begin + i), vr[lane], b[lane], recv_row, h, fl2);
+        if (flags_out) flags_out[i] = fl[lane] | fl2;
+        if (hash_out) hash_out[i] = h;
+        if (descending)
+          for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+      }
+      if (descending) { next_recv = above; n_valid_next = n_valid; }
+    }
+    // the lanes of a tile bump the counters one after the other here, not together as on the
+    // GPU: 64 per tile that replayed
+    g_replays += record_mem[kRecReplays] / 64u;
+    g_top_replays += record_mem[kTopReplays] / 64u;
+  }
+  if (n_from_tile) *n_from_tile = borrowed;
   return (int)q;
 }
+
+// cross-lane operations carried out by the last shim_schedules_tiles call, and how many of them
+// found lanes that had come from different places (must be 0)
+uint64_t shim_wave_operations(void) { return shim_wave::operations; }
+uint64_t shim_wave_mismatches(void) { return shim_wave::mismatches; }
 
 // the two XOR contributions of one row to the edge check
 void shim_edge_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row, uint64_t *xr,

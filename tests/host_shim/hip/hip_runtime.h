@@ -1,6 +1,12 @@
 // Stand-in for <hip/hip_runtime.h> that lets the per-rank device functions of
-// the HIP library be compiled by g++ and run on the CPU, one "lane" at a time.
-// Only what bcast_device.hpp uses is provided.
+// the HIP library be compiled by g++ and run on the CPU.  Only what
+// bcast_device.hpp uses is provided.
+//
+// Cross-lane operations go through shim_wave::cross_lane.  Inside
+// shim_wave::run the lanes of a wavefront are coroutines that meet at every
+// such operation, so __any, readfirstlane and the shuffles see the values of
+// all lanes that take part, as on the GPU; outside of it they are those of a
+// wavefront of one lane.
 #pragma once
 #include <stdint.h>
 
@@ -11,7 +17,13 @@
 static inline int __ffs(int x) { return x == 0 ? 0 : __builtin_ctz((unsigned)x) + 1; }
 static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
 static inline int __popc(unsigned x) { return __builtin_popcount(x); }
-// cross-lane operations for a wavefront of one lane
-static inline int __any(int pred) { return pred != 0; }
-static inline int __shfl_xor(int v, int, int) { return v; }
-static inline int __builtin_amdgcn_readfirstlane(int v) { return v; }
+
+namespace shim_wave {
+enum Op : int { kAny = 0, kShflXor = 1, kFirstLane = 2 };
+// `site` names the place in the source: lanes that meet must all come from the same one.
+int cross_lane(Op op, int value, int arg, int site);
+}  // namespace shim_wave
+
+#define __any(pred) shim_wave::cross_lane(shim_wave::kAny, (pred) ? 1 : 0, 0, __LINE__)
+#define __shfl_xor(v, mask, width) shim_wave::cross_lane(shim_wave::kShflXor, (v), (mask), __LINE__)
+#define __builtin_amdgcn_readfirstlane(v) shim_wave::cross_lane(shim_wave::kFirstLane, (v), 0, __LINE__)

@@ -35,9 +35,12 @@ def shim():
                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_edge_row.restype = None
     lib.shim_schedules_tiles.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
-                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_last_replays.restype = ctypes.c_uint64
+    lib.shim_wave_operations.restype = ctypes.c_uint64
+    lib.shim_wave_mismatches.restype = ctypes.c_uint64
     lib.shim_recv_two_ways.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
                                        ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_recv_two_ways.restype = ctypes.c_uint32
@@ -58,14 +61,19 @@ def shim_rows(lib, p, root, ranks):
     return rows, flags, hashes
 
 
-def shim_tiles(lib, p, root, r_begin, n):
+def shim_tiles(lib, p, root, r_begin, n, run_tiles=0, descending=True):
+    """Rows, flags and hashes of n consecutive ranks, computed tile by tile by a wavefront of 64
+    lanes on the CPU (runs of run_tiles tiles; 0 = one run), and the violations of Algorithm 6
+    that were answered from a neighbour's row."""
     q = oracle.q_of(p)
     rows = np.zeros((n, 2 * q), dtype=np.int32)
     flags = np.zeros(n, dtype=np.uint32)
     hashes = np.zeros(n, dtype=np.uint64)
     borrowed = ctypes.c_uint64(0)
-    lib.shim_schedules_tiles(p, root, r_begin, n, rows.ctypes.data if rows.size else None,
+    lib.shim_schedules_tiles(p, root, r_begin, n, run_tiles, int(descending),
+                             rows.ctypes.data if rows.size else None,
                              flags.ctypes.data, hashes.ctypes.data, ctypes.byref(borrowed))
+    assert int(lib.shim_wave_mismatches()) == 0       # the lanes met at the same operations
     return rows, flags, hashes, int(borrowed.value)
 
 
@@ -149,27 +157,35 @@ def test_edge_check_rows(shim):
 
 
 def test_replayed_lockstep_stretch_equals_the_search(shim):
-    # Ranks 64 apart (one lane of consecutive tiles) mostly arrive at the lockstep stretch of the
-    # receive search in the same shared state; the kernels then replay a recorded stretch instead
-    # of searching.  Whatever is replayed must equal Algorithm 5, everywhere a record can be taken
-    # over: long stretches of consecutive ranks at both ends and in the middle of several p.
+    # Consecutive tiles of a wavefront's run mostly arrive at the lockstep stretch of the receive
+    # search in the same shared state; the kernels then replay a recorded stretch instead of
+    # searching, and take the state after the top levels of the pass over from the tile before.
+    # Here a wavefront of 64 lanes runs on the CPU (lane-0 broadcasts, any, minimum and maximum
+    # over the 64 lanes' own values), so the checks that decide whether a record may be taken
+    # over see what they see on the GPU.  Whatever is replayed must equal Algorithm 5, everywhere
+    # a record can be taken over: long stretches of consecutive ranks at both ends and in the
+    # middle of several p, from the top down (kernels for p with violations) and from the bottom
+    # up (kernels for p = 2^q and 2^q - 1), in one run and in runs as short as the kernels'.
     replays = 0
     cases = [(2**31 - 1, 0, 2**30 - 30000, 60000), (2**31 - 1, 12345, 2**31 - 1 - 50000, 50000),
              (2**31 - 1, 0, 0, 40000), (1000003, 0, 0, 120000), (1000003, 999999, 880000, 120003),
              (805306373, 7, 402653000, 50000), (2**30 + 1, 2**29, 2**29 - 20000, 40000),
-             (65537, 1, 0, 65537), (4099, 0, 0, 4099), (3 * 2**20, 5, 2**20 - 10000, 30000)]
+             (65537, 1, 0, 65537), (4099, 0, 0, 4099), (3 * 2**20, 5, 2**20 - 10000, 30000),
+             (2**30, 2**29 + 7, 2**29 - 20000, 45000), (2**27 - 1, 5, 2**26 - 25000, 50001)]
     for p, root, a, n in cases:
-        rows, flags, _, _ = shim_tiles(shim, p, root, a, n)
-        replays_here = int(shim.shim_last_replays())
-        top_here = int(shim.shim_last_top_replays())
         want = oracle.schedules(p, root=root, r_begin=a, r_end=a + n, send_mode=1)
-        assert np.array_equal(rows, want), (p, root, a, n)
-        assert not flags.any()
-        replays += replays_here
-        if p > 10**6:
-            assert replays_here > n // 4, (p, replays_here)     # the record is actually used
-            assert top_here > n // 4, (p, top_here)
-    assert replays > 200000
+        for run_tiles, descending in [(0, True), (0, False), (6, True), (4, False), (3, False)]:
+            rows, flags, _, _ = shim_tiles(shim, p, root, a, n, run_tiles, descending)
+            replays_here = int(shim.shim_last_replays())
+            top_here = int(shim.shim_last_top_replays())
+            assert np.array_equal(rows, want), (p, root, a, n, run_tiles, descending)
+            assert not flags.any()
+            assert int(shim.shim_wave_operations()) > 0
+            replays += replays_here
+            if p > 10**6 and run_tiles == 0:
+                assert replays_here > n // 64 // 4, (p, replays_here)     # the record is actually used
+                assert top_here > n // 64 // 4, (p, top_here)
+    assert replays > 10000
 
 
 def test_level_helpers_against_the_skips(shim):

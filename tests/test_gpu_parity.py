@@ -6,6 +6,9 @@ by element; the full-size workloads are compared on what the oracle can
 recompute in seconds (whole tables where it can, seeded samples and
 order-free digests otherwise).
 """
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -19,6 +22,7 @@ from paper_2407_18004_amd import workloads  # noqa: E402
 from paper_2407_18004_amd.binding import VERDICT_BYTES, verdicts_from_bytes  # noqa: E402
 
 DEV = "cuda:0"
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -100,8 +104,7 @@ def test_workload1_small_sweep_simulation():
         got = gpu_simulate(p, n, [0])[0]
         assert got["flags"] == 0 and got["rounds"] == (n - 1 + q if q else 0), (p, got)
         assert got["first_bad"] == oracle.U64_MAX
-        if p % 16 == 1 or p < 300:
-            assert got == oracle.simulate(p, n, 0), p
+        assert got == oracle.simulate(p, n, 0), p
         clean += 1
     assert clean == workloads.SMALL_SWEEP_MAX_P
 
@@ -280,17 +283,30 @@ def test_workload2_materialised_instance():
 
 # ---------------------------------------------- workload 3: huge streamed --
 
+def streamed_golden():
+    """The oracle's digests of the 32 chunks (tests/golden/make_digest_golden.py --streamed)."""
+    with open(os.path.join(GOLDEN, "streamed_chunk_digests.json")) as fh:
+        gold = json.load(fh)
+    assert gold["p"] == workloads.STREAMED_P and gold["chunk"] == workloads.STREAMED_CHUNK
+    return gold
+
+
 def test_workload3_streamed_digests():
     p = workloads.STREAMED_P
     chunks = workloads.streamed_chunks()
     assert len(chunks) == 32
+    gold = streamed_golden()
     whole = 0
     per_chunk = []
-    for a, b in chunks:
+    for i, (a, b) in enumerate(chunks):
         dg, fl = gpu_digest(p, 0, a, b)
         assert fl == 0, (a, b, fl)
+        want = gold["chunks"][i]
+        assert (want["r_begin"], want["r_end"]) == (a, b)
+        assert f"{dg:016x}" == want["digest"] and want["flags"] == 0, (i, a, b)
         per_chunk.append(dg)
         whole ^= dg
+    assert f"{whole:016x}" == gold["digest"]
     # order-free digest: any other split of a chunk gives the same value
     a, b = chunks[5]
     cut = a + 12345677
@@ -303,6 +319,53 @@ def test_workload3_streamed_digests():
         assert gpu_digest(p, 0, lo, hi) == oracle.digest(p, 0, lo, hi, send_mode=1)
     # one call over the whole range equals the XOR of the chunks
     assert gpu_digest(p, 0, 0, p) == (whole, 0)
+
+
+@pytest.mark.parametrize("chunk", [0, 17, 31])
+def test_workload3_whole_chunks_against_the_oracle_live(chunk):
+    # Launches of the size and shape the benchmark times (2^26 ranks: every wavefront works
+    # through a run of several tiles and carries its records from tile to tile), digest and
+    # edge sums against the oracle computed here and now: the first chunk (with the root), one
+    # from the middle, and the last one, which is a rank short.
+    p = workloads.STREAMED_P
+    a, b = workloads.streamed_chunks()[chunk]
+    assert gpu_digest(p, 0, a, b) == oracle.digest(p, 0, a, b, send_mode=1)
+    assert gpu_edgecheck(p, 0, a, b) == oracle.edgecheck(p, 0, a, b, send_mode=1)
+
+
+@pytest.mark.parametrize("p,root,a,n", [
+    (2**30, 2**29 + 7, 2**29 - 2**23 + 11, 2**24 + 5),          # a power of two, the root inside
+    (2**27 - 1, 77_000_001, 77_000_001 - 9_000_000, 2**24 + 100_003),   # 2^q - 1, the root inside
+    (2**31 - 1, 2**31 - 2, 2**31 - 1 - 2**24 - 63, 2**24 + 63),  # the last ranks, root = p - 1
+])
+def test_long_launches_without_violations_against_the_oracle(p, root, a, n):
+    # p = 2^q and 2^q - 1 take the kernels whose wavefronts work alone; only launches of
+    # several million ranks give them runs of three and more tiles, where the records are used
+    b = a + n
+    assert b <= p
+    assert gpu_digest(p, root, a, b) == oracle.digest(p, root, a, b, send_mode=1)
+    assert gpu_edgecheck(p, root, a, b) == oracle.edgecheck(p, root, a, b, send_mode=1)
+
+
+@pytest.mark.parametrize("p,root,a", [
+    (2**31 - 1, 0, 0),
+    (2**31 - 1, 1_500_000_000, 1_500_000_000 - 5_000_000),
+    (2**30, 3, 2**29),
+])
+def test_long_tables_without_violations_slice_by_slice(p, root, a):
+    # one bcast_schedules launch of 2^24 + 77 ranks (4.2 GB at q = 31), compared with the
+    # oracle in slices of 2^21 ranks so that the host never holds the whole table
+    n = 2**24 + 77
+    q = lib.bcast_q(p)
+    t = torch.full((n, 2 * q), 99, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules(p, root, a, a + n, t, t, 2 * q, send_offset=q)
+    torch.cuda.synchronize()
+    step = 2**21
+    for lo in range(0, n, step):
+        hi = min(lo + step, n)
+        want = oracle.schedules(p, root=root, r_begin=a + lo, r_end=a + hi, send_mode=1)
+        assert np.array_equal(t[lo:hi].cpu().numpy(), want), (p, root, a + lo, a + hi)
+    del t
 
 
 def test_workload3_seeded_rank_sample_against_definition():
@@ -333,12 +396,18 @@ def test_edge_check_matches_oracle_and_holds_on_whole_instances():
 def test_workload3_edge_check_of_the_whole_instance():
     # Conditions 1 and 2 on all 31 * (2^31 - 1) edges, chunk by chunk
     p = workloads.STREAMED_P
+    gold = streamed_golden()
     xr = xs = 0
+    seen = []
     for a, b in workloads.streamed_chunks():
         r, s = gpu_edgecheck(p, 0, a, b)
         xr ^= r
         xs ^= s
+        want = gold["chunks"][len(seen)]
+        assert (f"{r:016x}", f"{s:016x}") == (want["edge_recv"], want["edge_send"]), (a, b)
+        seen.append((a, b))
     assert xr == xs
+    assert (f"{xr:016x}", f"{xs:016x}") == (gold["edge_recv"], gold["edge_send"])
     w = 1 << 21
     assert gpu_edgecheck(p, 0, 2**30 - w, 2**30 + w) == oracle.edgecheck(p, 0, 2**30 - w, 2**30 + w)
 
@@ -383,8 +452,8 @@ def test_workload4_batched_rejects_bad_input():
 
 
 def test_workload4_batched_full_size():
-    # 65,536 instances x 4,096 ranks, about 35 GB of schedules in HBM; the oracle
-    # recomputes a seeded subset of instances, the rest is checked by range.
+    # 65,536 instances x 4,096 ranks, about 35 GB of schedules in HBM, all of them
+    # compared with the oracle.
     n_inst, m = 65536, 4096
     p, root, _ = workloads.batched_instances(n_inst, m, seed=42, with_ranks=False)
     row_off = workloads.batched_row_offsets(p, m)
@@ -402,16 +471,19 @@ def test_workload4_batched_full_size():
                                 d(row_off, np.int64), out, rej)
     torch.cuda.synchronize()
     assert int(rej.item()) == 0
-    pick = workloads.counter_random(99, 1, np.arange(48)) % np.uint64(n_inst)
-    for i in [0, n_inst - 1] + [int(x) for x in pick]:
-        q = oracle.q_of(int(p[i]))
-        _, _, ranks = workloads.batched_instances(1, m, seed=42, first=i)
-        got = out[int(row_off[i]): int(row_off[i + 1])].cpu().numpy().reshape(m, 2 * q)
-        want = oracle.schedules_ranks(int(p[i]), int(root[i]), ranks[0], send_mode=1)
-        assert np.array_equal(got, want), i
-    # every entry of every instance lies in [-31, 30]
-    lo, hi = int(out.min().item()), int(out.max().item())
-    assert -31 <= lo and hi <= 30
+    # every row of every instance, element by element: the table comes back in blocks of 2,048
+    # instances (about 1.1 GB) and the oracle recomputes each instance's 4,096 rows
+    block = 2048
+    for first in range(0, n_inst, block):
+        got_block = out[int(row_off[first]): int(row_off[first + block])].cpu().numpy()
+        _, _, ranks = workloads.batched_instances(block, m, seed=42, first=first)
+        base = int(row_off[first])
+        for i in range(first, first + block):
+            q = oracle.q_of(int(p[i]))
+            got = got_block[int(row_off[i]) - base: int(row_off[i + 1]) - base].reshape(m, 2 * q)
+            want = oracle.schedules_ranks(int(p[i]), int(root[i]), ranks[i - first], send_mode=1)
+            assert np.array_equal(got, want), (i, int(p[i]), int(root[i]))
+        print(f"batched: instances [{first}, {first + block}) equal the oracle's", flush=True)
 
 
 # ------------------------------------------------ workload 5: simulation --

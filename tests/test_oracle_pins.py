@@ -453,6 +453,47 @@ def test_simulation_catches_planted_mistakes():
     assert vd["n_incomplete_ranks"] == p - 1
 
 
+def test_simulation_exact_verdict_of_a_corrupted_table_replayed_by_hand():
+    # p = 3 (q = 2, skips 1, 2, 3), n = 2 blocks, so x = (2 - 1 mod 2) mod 2 = 1 and the three
+    # rounds are i = 1, 2, 3 of Algorithm 1 (numbered 0, 1, 2 in the verdict).  The entry used in
+    # round i is raw[i mod 2] - 1 + 2 * (i div 2): raw[1] - 1, raw[0] + 1, raw[1] + 1.
+    # The correct table, from Conditions 1-4 by hand (b = 2, 0, 1):
+    #          recv       send
+    #   r = 0  -1 -2      0  1
+    #   r = 1   0 -1     -2 -2
+    #   r = 2  -2  1     -1 -1
+    good = np.array([[-1, -2, 0, 1], [0, -1, -2, -2], [-2, 1, -1, -1]], dtype=np.int32)
+    assert np.array_equal(oracle.schedules(3), good)
+    vd = oracle.simulate(3, 2, 0, good)
+    assert vd == {"flags": 0, "rounds": 3, "n_bad_recv_dup": 0, "n_bad_send_unheld": 0,
+                  "n_edge_mismatch": 0, "n_incomplete_ranks": 0, "first_bad": oracle.U64_MAX}
+    # Two planted mistakes: recvblock[0] of rank 1 is -1 instead of 0, sendblock[1] of rank 2 is
+    # 0 instead of -1.  Algorithm 1 by hand (blocks above n - 1 = 1 count as 1):
+    #   round 0 (k = 1, skip 2, entry raw - 1): rank 1 expects -2: nothing, and rank 2 sends
+    #     0 - 1 = -1: nothing; rank 2 expects 1 - 1 = 0 from the root, which sends 1 - 1 = 0: fine.
+    #   round 1 (k = 0, skip 1, entry raw + 1): rank 1 expects -1 + 1 = 0 from the root, which
+    #     sends 0 + 1 = 1: the blocks differ (one edge mismatch, round 1, rank 1); rank 1 marks
+    #     block 0.  Rank 2 expects -1: nothing; it would send -1 + 1 = 0 to the root: never sent.
+    #   round 2 (k = 1, skip 2, entry raw + 1): rank 1 expects -1 + 1 = 0 from rank 2, which
+    #     sends 0 + 1 = 1: a second edge mismatch, and rank 1 already holds block 0: one duplicate
+    #     receive (round 2, rank 1).  Rank 2 sends block 1 without having held it before the
+    #     round (it arrives from the root in this very round): one send of a block not held
+    #     (round 2, rank 2).  Rank 2 expects 1 + 1 = 2 -> 1 from the root (1 + 1 = 2 -> 1): fine.
+    #   end: rank 1 holds block 0 only: one incomplete rank (counted at round 3 = rounds).
+    #   first failure: round 1, rank 1.
+    bad = good.copy()
+    bad[1, 0] = -1
+    bad[2, 3] = 0
+    vd = oracle.simulate(3, 2, 0, bad)
+    assert vd == {"flags": 1 | 2 | 4 | 8, "rounds": 3, "n_bad_recv_dup": 1, "n_bad_send_unheld": 1,
+                  "n_edge_mismatch": 2, "n_incomplete_ranks": 1, "first_bad": (1 << 32) | 1}
+    # the same table with the processors renumbered by root 2 (physical rank = virtual + 2 mod 3):
+    # same counts, and the first failure is reported at physical rank (1 + 2) mod 3 = 0
+    vd = oracle.simulate(3, 2, 2, np.roll(bad, 2, axis=0))
+    assert vd == {"flags": 15, "rounds": 3, "n_bad_recv_dup": 1, "n_bad_send_unheld": 1,
+                  "n_edge_mismatch": 2, "n_incomplete_ranks": 1, "first_bad": (1 << 32) | 0}
+
+
 # -------------------------------------------------------------- digest ----
 
 def test_sm64_published_vectors():
@@ -510,6 +551,114 @@ def test_digest_row_flags_on_planted_mistakes():
     sw = recv.copy()
     sw[0], sw[1] = recv[1], recv[0]
     assert oracle.digest_row(p, 0, r, sw, send)[0] != h0
+
+
+# The hash of a row and of an edge are definitions of this build (the paper defines none); what
+# follows evaluates their written specification a second time, in plain Python integers, on the
+# rows the paper prints (Tables 1-3, read from the text fixtures, not from the oracle).
+
+def _sm64_py(z):
+    m = (1 << 64) - 1
+    z = (z + 0x9E3779B97F4A7C15) & m
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & m
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & m
+    return z ^ (z >> 31)
+
+
+def _row_hash_py(p, r, recv, send):
+    fields = [x + 32 for x in list(recv) + list(send)]           # six bits each
+    h = _sm64_py((p << 32) ^ r)
+    for i in range(0, len(fields), 10):                          # ten fields to a word
+        h = _sm64_py(h ^ sum(f << (6 * t) for t, f in enumerate(fields[i:i + 10])))
+    return h
+
+
+def test_sm64_second_implementation_and_the_published_vectors():
+    g = 0x9E3779B97F4A7C15
+    assert [_sm64_py(0), _sm64_py(g), _sm64_py(2 * g)] == \
+        [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+    # the published generator seeded with 1234567: state += g, then the output function
+    assert [_sm64_py((1234567 + i * g) & oracle.U64_MAX) for i in range(3)] == \
+        [6457827717110365317, 3203168211198807973, 9817491932198370423]
+    for z in (1, 2**63, oracle.U64_MAX, 0x0123456789ABCDEF):
+        assert oracle.sm64(z) == _sm64_py(z)
+
+
+@pytest.mark.parametrize("name", ["table1_p17.txt", "table2_p9.txt", "table3_p18.txt"])
+def test_row_hash_on_the_printed_tables_by_a_second_evaluation(name):
+    p, b, recv, send = read_table(name)
+    q = len(recv)
+    whole = 0
+    for r in range(p):
+        rr = [recv[k][r] for k in range(q)]
+        ss = [send[k][r] for k in range(q)]
+        want = _row_hash_py(p, r, rr, ss)
+        assert oracle.digest_row(p, 0, r, rr, ss) == (want, 0), (name, r)
+        whole ^= want
+    assert oracle.digest(p, 0, 0, p) == (whole, 0)
+    # a root other than 0: the row of physical rank r is the printed column (r - root) mod p,
+    # hashed under r
+    root = 5
+    whole = 0
+    for r in range(p):
+        v = (r - root) % p
+        whole ^= _row_hash_py(p, r, [recv[k][v] for k in range(q)], [send[k][v] for k in range(q)])
+    assert oracle.digest(p, root, 0, p) == (whole, 0)
+
+
+def test_row_hash_packing_against_words_worked_out_by_hand():
+    # Table 2, processor 1: recv 0 -2 -3 -1, send -4 -4 0 0; fields (value + 32):
+    # 32 30 29 31 28 28 32 32, eight of them, so one word:
+    # 32 + 30*2^6 + 29*2^12 + 31*2^18 + 28*2^24 + 28*2^30 + 32*2^36 + 32*2^42
+    w = 32 + 1920 + 118784 + 8126464 + 469762048 + 30064771072 + 2199023255552 + 140737488355328
+    assert w == 0x82071C7DD7A0
+    assert oracle.digest_row(9, 0, 1, [0, -2, -3, -1], [-4, -4, 0, 0])[0] == \
+        _sm64_py(_sm64_py((9 << 32) ^ 1) ^ w)
+    # Table 1, processor 3 (q = 5, ten fields, exactly one full word):
+    # recv -4 -5 2 -2 -1, send -3 -3 -4 2 2 -> fields 28 27 34 30 31 29 29 28 34 34
+    fields = [28, 27, 34, 30, 31, 29, 29, 28, 34, 34]
+    w = 0
+    for f in reversed(fields):            # field 0 ends up in the lowest six bits
+        w = w * 64 + f
+    assert w == 0x8A271D75F7A26DC and w < 2**60      # 100010 100010 011100 011101 011101 011111 011110 100010 011011 011100
+    assert oracle.digest_row(17, 0, 3, [-4, -5, 2, -2, -1], [-3, -3, -4, 2, 2])[0] == \
+        _sm64_py(_sm64_py((17 << 32) ^ 3) ^ w)
+    # p = 2^31 - 1 has 62 fields: six full words and a seventh with two fields; a row made of the
+    # extreme values -31 and 30 (fields 1 and 62) with its words written out
+    p, q = 2**31 - 1, 31
+    recv = [-31 if k % 2 == 0 else 30 for k in range(q)]
+    send = [30 if k % 2 == 0 else -31 for k in range(q)]
+    f = [x + 32 for x in recv + send]
+    assert f[:4] == [1, 62, 1, 62] and f[30:33] == [1, 62, 1] and len(f) == 62
+    h = _sm64_py((p << 32) ^ 12345)
+    for i in range(7):
+        h = _sm64_py(h ^ sum(x << (6 * t) for t, x in enumerate(f[10 * i: 10 * i + 10])))
+    assert oracle.digest_row(p, 0, 12345, recv, send)[0] == h
+
+
+@pytest.mark.parametrize("name", ["table1_p17.txt", "table2_p9.txt", "table3_p18.txt"])
+def test_edge_hash_on_the_printed_tables_by_a_second_evaluation(name):
+    # g(rank, k, val) = sm64(rank << 11 | k << 6 | (val + 32)); what r expects in round k under
+    # r, what it sends under its to-processor (r + skip[k]) mod p, skips from the table's bars
+    p, b, recv, send = read_table(name)
+    q = len(recv)
+    skip = {17: [1, 2, 3, 5, 9], 9: [1, 2, 3, 5], 18: [1, 2, 3, 5, 9]}[p]
+    xr = xs = 0
+    table = np.zeros((p, 2 * q), dtype=np.int32)
+    for r in range(p):
+        for k in range(q):
+            table[r, k], table[r, q + k] = recv[k][r], send[k][r]
+            xr ^= _sm64_py((r << 11) | (k << 6) | (recv[k][r] + 32))
+            xs ^= _sm64_py((((r + skip[k]) % p) << 11) | (k << 6) | (send[k][r] + 32))
+    assert xr == xs                                   # Conditions 1 and 2 hold on the printed table
+    assert oracle.edgecheck_table(p, table) == (xr, xs)
+    assert oracle.edgecheck(p, 0, 0, p) == (xr, xs)
+    one = 3                                           # a single rank's share
+    a = b2 = 0
+    for k in range(q):
+        a ^= _sm64_py((one << 11) | (k << 6) | (recv[k][one] + 32))
+        b2 ^= _sm64_py((((one + skip[k]) % p) << 11) | (k << 6) | (send[k][one] + 32))
+    assert oracle.edgecheck(p, 0, one, one + 1) == (a, b2)
 
 
 def test_digest_known_answers():

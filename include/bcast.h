@@ -200,6 +200,24 @@ int bcast_simulate_reduce(uint32_t p, uint32_t n, const uint32_t *roots, uint32_
                           const int32_t *sched, void *workspace, size_t workspace_bytes,
                           bcast_verdict *verdict, void *stream);
 
+/* bcast_simulate for callers that cannot allocate device memory and so cannot
+ * bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The same replay with the same kernels; the
+ * workspace is an array of BCAST_NOALLOC_SCRATCH_BYTES bytes that the library
+ * holds in the memory of every GPU it is used on, from the first call on that
+ * GPU until the process ends.  The call allocates and frees nothing and does
+ * not wait.  Instances that need more (bcast_simulate_workspace(p, n, n_roots)
+ * > BCAST_NOALLOC_SCRATCH_BYTES) are refused with BCAST_ENOMEM before anything
+ * is launched: p = 65,537 with n = 256 and one root needs 20 MB and fits, the
+ * same with 64 roots does not.  All calls on one GPU share the one array, which
+ * keeps what the last call left in it (nothing in it has to be cleared between
+ * calls); calls that overlap in time on one GPU, e.g. on two streams, race and
+ * give undefined verdicts: order them.  Other arguments and errors as for
+ * bcast_simulate; BCAST_EHIP also when the array's address cannot be had. */
+#define BCAST_NOALLOC_SCRATCH_BYTES (32u * 1024u * 1024u)
+int bcast_simulate_noalloc(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                           const int32_t *sched, bcast_verdict *verdict, void *stream);
+
 /* Text for a return code; never NULL. */
 const char *bcast_strerror(int code);
 

@@ -82,6 +82,8 @@ def load_library():
                                    ctypes.c_size_t, vp, vp]
     lib.bcast_simulate_reduce.argtypes = lib.bcast_simulate.argtypes
     lib.bcast_simulate_reduce.restype = ctypes.c_int
+    lib.bcast_simulate_noalloc.argtypes = [u32, u32, ctypes.POINTER(u32), u32, vp, vp, vp]
+    lib.bcast_simulate_noalloc.restype = ctypes.c_int
     lib.bcast_strerror.argtypes = [ctypes.c_int]
     lib.bcast_strerror.restype = ctypes.c_char_p
     for name in ("bcast_q", "bcast_skips", "bcast_schedules", "bcast_schedules_digest",
@@ -212,6 +214,16 @@ def bcast_simulate(p: int, n: int, roots, sched, workspace, verdict, stream=None
         _dev_ptr(workspace, torch.uint8, "workspace"),
         0 if workspace is None else workspace.numel(),
         _dev_ptr(verdict, torch.uint8, "verdict"), _stream_handle(stream)), _entry)
+
+
+def bcast_simulate_noalloc(p: int, n: int, roots, sched, verdict, stream=None) -> None:
+    """bcast_simulate on the library's own scratch array (no workspace argument)."""
+    import torch
+    roots = list(roots)
+    arr = (ctypes.c_uint32 * max(len(roots), 1))(*roots)
+    _check(load_library().bcast_simulate_noalloc(
+        p, n, arr, len(roots), _dev_ptr(sched, torch.int32, "sched"),
+        _dev_ptr(verdict, torch.uint8, "verdict"), _stream_handle(stream)), "bcast_simulate_noalloc")
 
 
 def verdicts_from_bytes(raw: bytes) -> list[dict]:

@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+#include <mutex>
 #include <type_traits>
 
 #include "../../include/bcast.h"
@@ -1314,11 +1315,55 @@ int bcast_simulate_reduce(uint32_t p, uint32_t n, const uint32_t *roots, uint32_
                        stream);
 }
 
+// ------------------------------------------------- the call that allocates nothing
+
+namespace {
+
+// The workspace of bcast_simulate for callers that cannot bring one: one array per GPU, there
+// from the moment the library's code is loaded on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[BCAST_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];          // the array's address on each device, once asked for
+std::mutex g_scratch_mutex;
+
+// The address of `scratch` on the current device (the array's name is no device address in host
+// code).  Asked for once per device, with that device current; nullptr if the runtime refuses.
+void *scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+int bcast_simulate_noalloc(uint32_t p, uint32_t n, const uint32_t *roots, uint32_t n_roots,
+                           const int32_t *sched, bcast_verdict *verdict, void *stream) {
+  const size_t need = bcast_simulate_workspace(p, n, n_roots);
+  if (need == 0) return BCAST_EINVAL;
+  if (need > (size_t)BCAST_NOALLOC_SCRATCH_BYTES) return BCAST_ENOMEM;
+  void *ptr = scratch_on_current_device();
+  if (ptr == nullptr) return BCAST_EHIP;
+  // Nothing in the array has to start at zero: the replay clears the possession words it uses,
+  // and the roots and the table are written before they are read.
+  return simulate_impl(false, p, n, roots, n_roots, sched, ptr, (size_t)BCAST_NOALLOC_SCRATCH_BYTES,
+                       verdict, stream);
+}
+
 const char *bcast_strerror(int code) {
   switch (code) {
     case BCAST_OK: return "ok";
     case BCAST_EINVAL: return "argument outside the documented domain";
-    case BCAST_ENOMEM: return "workspace too small";
+    case BCAST_ENOMEM: return "workspace too small (bcast_simulate_noalloc: the replay needs more than BCAST_NOALLOC_SCRATCH_BYTES)";
     case BCAST_EHIP: return "HIP runtime error";
     default: return "unknown bcast error code";
   }

@@ -140,6 +140,29 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin,
  * overlapping tables. */
 int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *stream);
 
+/* The baseblocks of all p processors in linear time, as in the proof of
+ * Lemma 4: starting from the list of one rank, the list for the first skip[k+1]
+ * ranks is the list for the first skip[k] ranks followed by a copy of its first
+ * skip[k+1] - skip[k] entries, with the root's entry raised to k + 1 afterwards
+ * (0 -> 10 -> 201 -> 301201 -> ...).  list: device, p bytes, list[r] = b_r in
+ * [0, q] (q for the root, as Algorithm 3 returns it).  One copy per skip, 2p
+ * bytes moved in all; no search and no per-rank loop.  Errors: p outside the
+ * domain, NULL. */
+int bcast_baseblocks(uint32_t p, uint8_t *list, void *stream);
+
+/* The whole table for root 0, int32 [p][2q] as bcast_schedules writes it with
+ * ld = 2q, by Observations 1 and 5 wherever they apply: with p = m 2^j, m odd,
+ * the table of m is computed by Algorithms 3, 5 and 6 and doubled j times
+ * (bcast_schedules_double), so the O(p log p) search runs for p / 2^j ranks
+ * only and the rest is data movement.  Odd p: the same as bcast_schedules.
+ * workspace: device, at least bcast_schedules_doubling_workspace(p) bytes (the
+ * tables of p/2 and p/4), contents irrelevant on entry, must not overlap out.
+ * Errors: p outside the domain, NULL pointers, overlap; BCAST_ENOMEM when the
+ * workspace is too small. */
+size_t bcast_schedules_doubling_workspace(uint32_t p);
+int bcast_schedules_doubling(uint32_t p, int32_t *out, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 /* Algorithms 3, 5 (with 4) and 6 for listed ranks of many instances at once (the
  * skips of Algorithm 2 per instance): instance i has p[i] processors, root[i]
  * (renumbering as in Section 2), and asks for the m physical ranks

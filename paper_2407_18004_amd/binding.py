@@ -82,6 +82,12 @@ def load_library():
                                    ctypes.c_size_t, vp, vp]
     lib.bcast_simulate_reduce.argtypes = lib.bcast_simulate.argtypes
     lib.bcast_simulate_reduce.restype = ctypes.c_int
+    lib.bcast_baseblocks.argtypes = [u32, vp, vp]
+    lib.bcast_baseblocks.restype = ctypes.c_int
+    lib.bcast_schedules_doubling_workspace.argtypes = [u32]
+    lib.bcast_schedules_doubling_workspace.restype = ctypes.c_size_t
+    lib.bcast_schedules_doubling.argtypes = [u32, vp, vp, ctypes.c_size_t, vp]
+    lib.bcast_schedules_doubling.restype = ctypes.c_int
     lib.bcast_simulate_noalloc.argtypes = [u32, u32, ctypes.POINTER(u32), u32, vp, vp, vp]
     lib.bcast_simulate_noalloc.restype = ctypes.c_int
     lib.bcast_strerror.argtypes = [ctypes.c_int]
@@ -190,6 +196,30 @@ def bcast_schedules_batched(n_inst: int, p, root, ranks, m: int, row_off, out,
         _dev_ptr(out, torch.int32, "out"), 0 if out is None else out.numel(),
         _dev_ptr(n_rejected, torch.int32, "n_rejected"), _stream_handle(stream)),
         "bcast_schedules_batched")
+
+
+def bcast_baseblocks(p: int, out, stream=None) -> None:
+    """out: device uint8 tensor of p elements; out[r] = baseblock of rank r (root 0)."""
+    import torch
+    if out is None or out.numel() < p:
+        raise ValueError("out must hold p bytes")
+    _check(load_library().bcast_baseblocks(p, _dev_ptr(out, torch.uint8, "out"), _stream_handle(stream)),
+           "bcast_baseblocks")
+
+
+def bcast_schedules_doubling_workspace(p: int) -> int:
+    return int(load_library().bcast_schedules_doubling_workspace(p))
+
+
+def bcast_schedules_doubling(p: int, out, workspace, stream=None) -> None:
+    """out: device int32 tensor [p][2q]; workspace: device uint8 tensor."""
+    import torch
+    q = bcast_q(p)
+    if out is not None and out.numel() < p * 2 * q:
+        raise ValueError("out must hold p * 2q int32 elements")
+    _check(load_library().bcast_schedules_doubling(
+        p, _dev_ptr(out, torch.int32, "out"), _dev_ptr(workspace, torch.uint8, "workspace"),
+        0 if workspace is None else workspace.numel(), _stream_handle(stream)), "bcast_schedules_doubling")
 
 
 def bcast_simulate_workspace(p: int, n: int, n_roots: int) -> int:

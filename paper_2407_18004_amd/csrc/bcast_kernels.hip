@@ -585,6 +585,51 @@ __global__ __launch_bounds__(kBlock) void k_double(DoubleParams prm) {
   }
 }
 
+// ------------------------------------------------- baseblocks in linear time
+
+// One step of the listing in the proof of Lemma 4: the baseblocks of the first skip[k] ranks are
+// known; those of the ranks skip[k] .. skip[k+1]-1 are a copy of the first skip[k+1] - skip[k]
+// of them (rank skip[k] takes the root's old entry k), and the root's entry becomes k + 1.
+// `done` = skip[k], `upto` = skip[k+1] <= 2 done: source and destination never overlap.
+__global__ __launch_bounds__(kBlock) void k_listing_step(uint8_t *list, uint32_t done, uint32_t upto) {
+  const uint64_t n = (uint64_t)upto - done;                  // bytes to copy from list[0..n) to list[done..upto)
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  const uint64_t tid = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+  // Destination in 16-byte groups from its first 16-byte boundary on; the source of a group
+  // starts at any byte: five aligned words, shifted into place.  Ends by single bytes.
+  const uintptr_t dst0 = reinterpret_cast<uintptr_t>(list) + done;
+  uint64_t head = (16u - (dst0 & 15u)) & 15u;
+  head = head < n ? head : n;
+  const uint64_t n16 = (reinterpret_cast<uintptr_t>(list) & 3u) == 0u ? (n - head) / 16u : 0u;
+  const uint32_t *words = reinterpret_cast<const uint32_t *>(list);
+  uint4 *dst = reinterpret_cast<uint4 *>(list + done + head);
+  for (uint64_t g = tid; g < n16; g += stride) {
+    const uint64_t src = head + 16u * g;                     // byte offset of the group's source
+    const uint64_t w = src >> 2;
+    const uint32_t sh = (uint32_t)(src & 3u);
+    // src + 16 <= n <= done: the bytes that are used all lie in list[0 .. n); the fifth word may
+    // reach up to byte done + 2 < upto (allocated; what it holds beyond byte n is shifted out)
+    const uint32_t a = words[w], b = words[w + 1], c = words[w + 2], d = words[w + 3];
+    uint4 o;
+    if (sh == 0u) {
+      o.x = a; o.y = b; o.z = c; o.w = d;
+    } else {
+      const uint32_t e = words[w + 4];
+      o.x = __builtin_amdgcn_alignbyte(b, a, sh);
+      o.y = __builtin_amdgcn_alignbyte(c, b, sh);
+      o.z = __builtin_amdgcn_alignbyte(d, c, sh);
+      o.w = __builtin_amdgcn_alignbyte(e, d, sh);
+    }
+    dst[g] = o;
+  }
+  for (uint64_t b = tid; b < head; b += stride) list[done + b] = list[b];
+  for (uint64_t b = head + n16 * 16u + tid; b < n; b += stride) list[done + b] = list[b];
+}
+
+__global__ void k_listing_root(uint8_t *list, uint32_t entry) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) list[0] = (uint8_t)entry;
+}
+
 // ------------------------------------------------------------------ batched
 
 struct BatchParams {
@@ -1193,6 +1238,88 @@ int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *st
   const size_t lds = (size_t)kWavesPerBlock * (slice_words(prm.q) + 2u * slice_words(prm.q + 1u)) * 4u;
   hipLaunchKernelGGL(k_double, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+int bcast_baseblocks(uint32_t p, uint8_t *list, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || !list) return BCAST_EINVAL;
+  const int cap = persistent_grid(UINT64_MAX);
+  if (cap < 0) return BCAST_EHIP;
+  hipStream_t st = (hipStream_t)stream;
+  // list of one rank: the root with entry 0; then one step per skip
+  hipLaunchKernelGGL(k_listing_root, dim3(1), dim3(64), 0, st, list, 0u);
+  if (!launch_ok()) return BCAST_EHIP;
+  uint32_t skips[32];
+  bcast_skips(p, skips, nullptr);
+  for (int k = 0; k < q; ++k) {
+    const uint64_t n = (uint64_t)skips[k + 1] - skips[k];
+    if (n > 0) {
+      const uint64_t want = (n / 16u + kBlock - 1) / kBlock + 1u;
+      const int grid = (int)(want < (uint64_t)cap ? want : (uint64_t)cap);
+      hipLaunchKernelGGL(k_listing_step, dim3(grid), dim3(kBlock), 0, st, list, skips[k], skips[k + 1]);
+      if (!launch_ok()) return BCAST_EHIP;
+    }
+    // the root's entry changes after the copy has read it (same stream: in order)
+    hipLaunchKernelGGL(k_listing_root, dim3(1), dim3(64), 0, st, list, (uint32_t)k + 1u);
+    if (!launch_ok()) return BCAST_EHIP;
+  }
+  return BCAST_OK;
+}
+
+size_t bcast_schedules_doubling_workspace(uint32_t p) {
+  const int q = host_q(p);
+  if (q < 0) return 0;
+  uint32_t j = 0;
+  while (j < 31u && ((p >> j) & 1u) == 0u) ++j;          // p = m 2^j, m odd
+  if (j == 0) return 256;                                 // odd p: nothing to double
+  size_t bytes = 256;
+  for (uint32_t i = 1; i <= 2u && i <= j; ++i) {          // the tables of p/2 and p/4
+    const uint32_t pi = p >> i;
+    const int qi = host_q(pi);
+    bytes += align_up((size_t)pi * 2u * (size_t)qi * 4u, 256);
+  }
+  return bytes;
+}
+
+int bcast_schedules_doubling(uint32_t p, int32_t *out, void *workspace, size_t workspace_bytes,
+                             void *stream) {
+  const int q = host_q(p);
+  if (q < 0) return BCAST_EINVAL;
+  if (q == 0) return BCAST_OK;
+  if (!out) return BCAST_EINVAL;
+  uint32_t j = 0;
+  while (j < 31u && ((p >> j) & 1u) == 0u) ++j;
+  if (j == 0) return bcast_schedules(p, 0, 0, p, out, out + q, 2 * (int64_t)q, stream);
+  const size_t need = bcast_schedules_doubling_workspace(p);
+  if (!workspace) return BCAST_EINVAL;
+  if (workspace_bytes < need) return BCAST_ENOMEM;
+  if (persistent_grid(1) < 0) return BCAST_EHIP;
+  // two buffers: A holds the tables of p/2, p/8, ..., B those of p/4, p/16, ...
+  uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256);
+  int32_t *buf_a = reinterpret_cast<int32_t *>(base);
+  base += align_up((size_t)(p >> 1) * 2u * (size_t)host_q(p >> 1) * 4u, 256);
+  int32_t *buf_b = reinterpret_cast<int32_t *>(base);
+  // the caller's table must not overlap the workspace that is in use
+  {
+    const uintptr_t o0 = reinterpret_cast<uintptr_t>(out), o1 = o0 + (size_t)p * 2u * (size_t)q * 4u;
+    const uintptr_t w0 = reinterpret_cast<uintptr_t>(workspace), w1 = w0 + need;
+    if (o0 < w1 && w0 < o1) return BCAST_EINVAL;
+  }
+  auto buffer_of = [&](uint32_t halvings) { return (halvings & 1u) ? buf_a : buf_b; };   // table of p >> halvings
+  const uint32_t m = p >> j;
+  const int qm = host_q(m);
+  int32_t *cur = buffer_of(j);
+  if (qm > 0) {
+    const int rc = bcast_schedules(m, 0, 0, m, cur, cur + qm, 2 * (int64_t)qm, stream);
+    if (rc != BCAST_OK) return rc;
+  }
+  for (uint32_t h = j; h >= 1u; --h) {                   // table of p >> (h - 1) from that of p >> h
+    int32_t *next = h == 1u ? out : buffer_of(h - 1u);
+    const int rc = bcast_schedules_double(p >> h, (p >> h) > 1u ? cur : nullptr, next, stream);
+    if (rc != BCAST_OK) return rc;
+    cur = next;
+  }
+  return BCAST_OK;
 }
 
 int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *root,

@@ -636,3 +636,69 @@ def test_doubling_chain_from_the_gpu_table_and_errors():
         lib.bcast_schedules_double(2**30, cur, cur)
     with pytest.raises(lib.BcastError):
         lib.bcast_schedules_double(1000008, cur, cur)          # overlap
+
+
+def test_schedules_by_doubling_equal_the_oracle():
+    # table(p) for p = m 2^j as table(m) doubled j times, against the oracle's table(p):
+    # powers of two (m = 1), twice an odd number, 3 * 2^20, workload 2's neighbour, odd p
+    for p in [1, 2, 4, 6, 12, 18, 64, 1000, 1001, 4096, 65536, 999_998, 1_000_004, 3 * 2**20, 2**22]:
+        q = lib.bcast_q(p)
+        ws = torch.full((lib.bcast_schedules_doubling_workspace(p),), 0x5A, dtype=torch.uint8, device=DEV)
+        out = torch.full((p, 2 * q), 77, dtype=torch.int32, device=DEV)
+        lib.bcast_schedules_doubling(p, out, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.schedules(p)), p
+    p = 1_000_004
+    q = lib.bcast_q(p)
+    out = torch.empty((p, 2 * q), dtype=torch.int32, device=DEV)
+    small = torch.empty(lib.bcast_schedules_doubling_workspace(p) - 1, dtype=torch.uint8, device=DEV)
+    with pytest.raises(lib.BcastError) as e:
+        lib.bcast_schedules_doubling(p, out, small)
+    assert e.value.code == lib.BCAST_ENOMEM
+    with pytest.raises(lib.BcastError):               # the table inside the workspace
+        big = torch.empty(p * 2 * q * 4 + lib.bcast_schedules_doubling_workspace(p), dtype=torch.uint8, device=DEV)
+        lib.bcast_schedules_doubling(p, big[: p * 2 * q * 4].view(torch.int32), big)
+    torch.cuda.synchronize()
+
+
+def test_baseblock_listing_in_linear_time():
+    # the listing of Lemma 4's proof on the GPU against Algorithm 3 of the oracle: every rank of
+    # every p <= 4096 (the baseblock is the one non-negative entry of the receive row, which the
+    # oracle takes from Algorithm 3; the root has q), direct calls of Algorithm 3 on samples,
+    # and all ranks of three large p
+    def want_list(p):
+        q = oracle.q_of(p)
+        b = oracle.schedules(p)[:, :q].max(axis=1, initial=-1).astype(np.int64)
+        b[0] = q
+        return b
+    rng = np.random.default_rng(4)
+    for p in list(range(1, 4097)) + [65537, 1_000_003, 2**22, 3 * 2**20 + 1]:
+        lst = torch.full((p + 3,), 200, dtype=torch.uint8, device=DEV)
+        view = lst[:p] if p % 2 else lst[3:3 + p]          # also from an address that is not aligned
+        lib.bcast_baseblocks(p, view)
+        torch.cuda.synchronize()
+        got = view.cpu().numpy().astype(np.int64)
+        assert np.array_equal(got, want_list(p)), p
+        for r in {0, min(1, p - 1), p - 1, p // 2} | {int(x) for x in rng.integers(0, p, size=4)}:
+            assert got[r] == oracle.baseblock(p, r), (p, r)
+        rest = (lst[p:] if p % 2 else lst[:3]).cpu().numpy()
+        assert (rest == 200).all()                          # nothing written outside the list
+    # p = 2^31 - 1: two gigabytes of baseblocks; powers of two all the way, so b_r is the
+    # position of the lowest set bit of r, and samples against Algorithm 3
+    p = 2**31 - 1
+    lst = torch.empty(p, dtype=torch.uint8, device=DEV)
+    lib.bcast_baseblocks(p, lst)
+    torch.cuda.synchronize()
+    for lo in (0, 2**30 - 5000, p - 2**20):
+        got = lst[lo: lo + 2**20].cpu().numpy().astype(np.int64)
+        r = np.arange(lo, lo + 2**20, dtype=np.int64)
+        want = np.zeros_like(r)
+        rr = r.copy()
+        rr[rr == 0] = 1
+        low = rr & -rr
+        want = np.log2(low).astype(np.int64)
+        if lo == 0:
+            want[0] = 31
+        assert np.array_equal(got, want), lo
+        for x in rng.integers(lo, lo + 2**20, size=8):
+            assert got[int(x) - lo] == oracle.baseblock(p, int(x))

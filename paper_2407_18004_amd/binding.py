@@ -82,6 +82,13 @@ def load_library():
                                    ctypes.c_size_t, vp, vp]
     lib.bcast_simulate_reduce.argtypes = lib.bcast_simulate.argtypes
     lib.bcast_simulate_reduce.restype = ctypes.c_int
+    lib.bcast_schedules_workspace.argtypes = [u32]
+    lib.bcast_schedules_workspace.restype = ctypes.c_size_t
+    lib.bcast_schedules_ws.argtypes = [u32, u32, u64, u64, vp, vp, i64, vp, ctypes.c_size_t, vp]
+    lib.bcast_schedules_digest_ws.argtypes = [u32, u32, u64, u64, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.bcast_schedules_edgecheck_ws.argtypes = [u32, u32, u64, u64, vp, vp, ctypes.c_size_t, vp]
+    for name in ("bcast_schedules_ws", "bcast_schedules_digest_ws", "bcast_schedules_edgecheck_ws"):
+        getattr(lib, name).restype = ctypes.c_int
     lib.bcast_baseblocks.argtypes = [u32, vp, vp]
     lib.bcast_baseblocks.restype = ctypes.c_int
     lib.bcast_schedules_doubling_workspace.argtypes = [u32]
@@ -153,6 +160,45 @@ def bcast_schedules(p: int, root: int, r_begin: int, r_end: int, recv, send, ld:
         sp += 4 * send_offset
     _check(load_library().bcast_schedules(p, root, r_begin, r_end, rp, sp, ld,
                                           _stream_handle(stream)), "bcast_schedules")
+
+
+def bcast_schedules_workspace(p: int) -> int:
+    return int(load_library().bcast_schedules_workspace(p))
+
+
+def bcast_schedules_ws(p: int, root: int, r_begin: int, r_end: int, recv, send, ld: int,
+                       workspace, stream=None, send_offset: int = 0) -> None:
+    """bcast_schedules with a device workspace (uint8 tensor of bcast_schedules_workspace(p) bytes)."""
+    import torch
+    rp = _dev_ptr(recv, torch.int32, "recv")
+    sp = _dev_ptr(send, torch.int32, "send")
+    if sp:
+        sp += 4 * send_offset
+    _check(load_library().bcast_schedules_ws(
+        p, root, r_begin, r_end, rp, sp, ld, _dev_ptr(workspace, torch.uint8, "workspace"),
+        0 if workspace is None else workspace.numel(), _stream_handle(stream)), "bcast_schedules_ws")
+
+
+def bcast_schedules_digest_ws(p: int, root: int, r_begin: int, r_end: int, digest, flags, workspace,
+                              stream=None) -> None:
+    import torch
+    _check(load_library().bcast_schedules_digest_ws(
+        p, root, r_begin, r_end, _dev_ptr(digest, torch.int64, "digest"),
+        _dev_ptr(flags, torch.int32, "flags"), _dev_ptr(workspace, torch.uint8, "workspace"),
+        0 if workspace is None else workspace.numel(), _stream_handle(stream)),
+        "bcast_schedules_digest_ws")
+
+
+def bcast_schedules_edgecheck_ws(p: int, root: int, r_begin: int, r_end: int, xors, workspace,
+                                 stream=None) -> None:
+    import torch
+    if xors is not None and xors.numel() < 2:
+        raise TypeError("xors: two elements are written")
+    _check(load_library().bcast_schedules_edgecheck_ws(
+        p, root, r_begin, r_end, _dev_ptr(xors, torch.int64, "xors"),
+        _dev_ptr(workspace, torch.uint8, "workspace"),
+        0 if workspace is None else workspace.numel(), _stream_handle(stream)),
+        "bcast_schedules_edgecheck_ws")
 
 
 def bcast_schedules_digest(p: int, root: int, r_begin: int, r_end: int, digest, flags,

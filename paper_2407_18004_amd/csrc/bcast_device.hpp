@@ -210,7 +210,9 @@ __device__ __forceinline__ TopDown top_down_start(uint32_t p, uint32_t v) {
 // kTrack: every test whose outcome depends on v also lowers `margin` to its
 // flip distance (tests between constants of the instance are left out; a test
 // that is not consulted may be included, which only makes the margin smaller).
-template <bool kSend, bool kTrack, typename EmitSend>
+// kDescent = false leaves the descent out (W, pathr, closed and anom are not touched): for the
+// deep levels of a rank whose descent comes from the table of deep entries (see DeepEntry).
+template <bool kSend, bool kTrack, bool kDescent = true, typename EmitSend>
 __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_t j, TopDown &s,
                                                uint32_t &margin, EmitSend emit_send) {
   auto see = [&](uint32_t x, uint32_t y) {
@@ -242,6 +244,7 @@ __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_
   const bool closes = !lower && rem_new == 0u;          // this level is the baseblock's
   s.jb = lower ? s.jb : j;
   s.rem = rem_new;
+  if (!kDescent) return;
   const int ski = (int)sk;
   const int t = s.W - ski;
   see((uint32_t)(t + 1), 0u);
@@ -370,31 +373,55 @@ __device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *
 //
 // The descent is made by the caller (top_down_level, together with Algorithms 3
 // and 6, which walk over the same levels): W, pathr and anom_in are its result.
+struct AscentState {
+  uint32_t D, M, sk1, k, j, live, pathr;
+};
+
+// State of the search after the descent (W, pathr as top_down_level leaves them), including the
+// accept at the bottom of the descent if there was one.
 template <typename Emit>
-__device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32_t q,
-                                                uint32_t jb, uint32_t k_last, int W,
-                                                uint32_t pathr, uint32_t anom_in,
-                                                bool &anomaly, Emit emit,
-                                                LockstepCache &cache, bool use_cache) {
-  const int b = (int)q - (int)jb;
-  uint32_t anom = anom_in;
+__device__ __forceinline__ AscentState ascent_start(uint32_t pm1, uint32_t q, uint32_t jb, int W,
+                                                    uint32_t pathr, Emit emit) {
+  AscentState a;
   const bool hit = W == -1;
   // The accept, if any, was the last level taken: the deepest bit of pathr.
   const uint32_t jd = hit ? 31u - (uint32_t)(__ffs((int)pathr) - 1) : 0u;
-  pathr = hit ? pathr & (pathr - 1u) : pathr;
-  uint32_t live = (q >= 31 ? 0xFFFFFFFFu : ((2u << q) - 1u)) & ~(1u << jb);
-  uint32_t D = hit ? (uint32_t)skip_at_level(pm1, jd) + 1u : (uint32_t)(W + 2);
-  uint32_t k = 0, j = kEndLevel;
-  uint32_t M = 1u;                                        // max(skip[k], Sd + 1)
-  uint32_t sk1 = 2u;                                      // skip[k + 1]
+  a.pathr = hit ? pathr & (pathr - 1u) : pathr;
+  a.live = (q >= 31 ? 0xFFFFFFFFu : ((2u << q) - 1u)) & ~(1u << jb);
+  a.D = hit ? (uint32_t)skip_at_level(pm1, jd) + 1u : (uint32_t)(W + 2);
+  a.k = 0; a.j = kEndLevel;
+  a.M = 1u;                                               // max(skip[k], Sd + 1)
+  a.sk1 = 2u;                                             // skip[k + 1]
   if (hit) {                                              // round 0 accepted at level jd
     emit(0u, -(int)jd);
-    live &= ~(1u << jd);
-    k = 1;
-    M = 2u;                                               // skip[1] = 2, Sd = 1
-    sk1 = q >= 2 ? skip_at_level(pm1, q - 2) : 0xFFFFFFFFu;
-    j = next_level(live, jd);
+    a.live &= ~(1u << jd);
+    a.k = 1;
+    a.M = 2u;                                             // skip[1] = 2, Sd = 1
+    a.sk1 = q >= 2 ? skip_at_level(pm1, q - 2) : 0xFFFFFFFFu;
+    a.j = next_level(a.live, jd);
   }
+  return a;
+}
+
+// Levels whose skip is below kLockstepSkip, as a mask; first_deep_level is the lowest of them.
+__device__ __forceinline__ uint32_t first_deep_level(uint32_t pm1) {
+  return pm1 >= kLockstepSkip ? 32u - (uint32_t)__clz((int)(pm1 / kLockstepSkip)) : 0u;
+}
+__device__ __forceinline__ uint32_t deep_level_mask(uint32_t pm1) {
+  const uint32_t first_deep = first_deep_level(pm1);
+  return first_deep < 32u ? 0xFFFFFFFFu << first_deep : 0u;
+}
+
+// The ascent from state `a` on.  kPrefix: only the first stretch (while levels with small skips
+// remain), with `a` holding the state it ends in; a search that stops there because it runs out of
+// pending calls is complete as far as it goes and raises nothing.
+template <bool kPrefix, typename Emit>
+__device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_t jb, uint32_t k_last,
+                                               AscentState &a, uint32_t anom_in, bool &anomaly,
+                                               Emit emit, LockstepCache &cache, bool use_cache) {
+  const int b = (int)q - (int)jb;
+  uint32_t anom = anom_in;
+  uint32_t D = a.D, M = a.M, sk1 = a.sk1, k = a.k, j = a.j, live = a.live, pathr = a.pathr;
   // Ascent.
   const uint32_t k_stop = k_last + 1u < q ? k_last + 1u : q;
   const uint32_t cap = 8u * q + 16u;
@@ -403,13 +430,7 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
   // and agree, move for move, once those are all accepted.  The first loop
   // lets every lane finish its deep levels and wait; the second then runs with
   // all lanes making the same move, so each iteration takes one branch only.
-  uint32_t deep = 0;                        // levels whose skip is below kLockstepSkip
-  if (pm1 >= kLockstepSkip) {
-    const uint32_t first_deep = 32u - (uint32_t)__clz((int)(pm1 / kLockstepSkip));
-    deep = first_deep < 32u ? 0xFFFFFFFFu << first_deep : 0u;
-  } else {
-    deep = 0xFFFFFFFFu;
-  }
+  const uint32_t deep = deep_level_mask(pm1);   // levels whose skip is below kLockstepSkip
   bool go = k < k_stop && !((int)j < 0 && pathr == 0);
   uint32_t it = 0;
   uint32_t margin = 0xFFFFFFFFu;
@@ -467,6 +488,11 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
     go = k < k_stop && !((int)j < 0 && pathr == 0);
   };
   for (; it < cap && go && (live & deep) != 0u; ++it) move(TrackOff{});
+  if (kPrefix) {
+    a.D = D; a.M = M; a.sk1 = sk1; a.k = k; a.j = j; a.live = live; a.pathr = pathr;
+    anomaly = anomaly || anom != 0 || it >= cap;
+    return k;
+  }
   // Lockstep stretch: replayed, recorded, or simply run.
   bool replayed = false, record = false;
   uint32_t D_in = D, M_in = M, k_in = k, live_in = live, pathr_in = pathr, j_in = j, it_in = it;
@@ -515,20 +541,118 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
   return k;
 }
 
+template <typename Emit>
+__device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32_t q,
+                                                uint32_t jb, uint32_t k_last, int W,
+                                                uint32_t pathr, uint32_t anom_in,
+                                                bool &anomaly, Emit emit,
+                                                LockstepCache &cache, bool use_cache) {
+  (void)p;
+  AscentState a = ascent_start(pm1, q, jb, W, pathr, emit);
+  return ascent_run<false>(pm1, q, jb, k_last, a, anom_in, anomaly, emit, cache, use_cache);
+}
+
+// Table of deep entries.
+//
+// The levels whose skip is below kLockstepSkip ("deep" levels, first_deep_level .. q) see of a rank
+// v only rho, what Algorithm 3 has left of v after the levels above them (rho < S, S the smallest
+// skip above the deep levels): for rho >= 2 the baseblock's level is a deep one and a function of
+// rho, the descent of the receive search arrives there with W = rho - 2, and the search then moves
+// among the deep levels exactly as it does for every other rank with the same rho, until it has
+// to go back to a call that is pending at a level above them (or has accepted all deep levels).
+// That stretch, the same for some p / S ranks, is computed once per rho and kept in a table in
+// device memory: the level of the baseblock, the levels accepted for rounds 0 .. K-1, and the
+// state in which the search goes on (remaining deep levels, D, M; the cursor is past the end of
+// the list and no deep call is pending).  16 bytes per rho:
+//   x: bits 0-10 remaining deep levels (bit i: level first_deep + i), 11-14 baseblock's level
+//      - first_deep, 15-18 K, bit 31 valid
+//   y: D | M << 16
+//   z, w: accepted levels - first_deep, four bits each, round k at nibble k (z: rounds 0-7)
+// rho < 2 (the baseblock's level lies above, or the descent has ended there) has no entry: such
+// ranks take the levels one by one.
+struct DeepTable {
+  const uint4 *entries;             // kDeepMaxEntries of them, or null
+  uint32_t first_deep;              // first deep level (>= 5 when the table is in use)
+  uint32_t n_rho;                   // S: entries exist for rho < S
+};
+
+constexpr uint32_t kDeepMaxEntries = 2u * kLockstepSkip + 2u;   // S <= 2 kLockstepSkip + 1
+constexpr uint32_t kDeepMinUpperLevels = 4u;
+
+__device__ __forceinline__ uint32_t deep_table_rhos(uint32_t pm1, uint32_t first_deep) {
+  return first_deep >= 1u ? skip_at_level(pm1, first_deep - 1u) : 0u;
+}
+
+// The entry of rho, computed the way every rank with that rho would: the deep levels of the pass
+// from the state in which the levels above leave them, then the search while it stays among
+// the deep levels.
+__device__ __forceinline__ uint4 deep_entry_build(uint32_t pm1, uint32_t q, uint32_t first_deep,
+                                                  uint32_t rho) {
+  uint4 e;
+  e.x = 0; e.y = 0; e.z = 0; e.w = 0;
+  if (rho < 2u) return e;
+  TopDown s;
+  s.rem = rho; s.jb = 0; s.closed = false;
+  s.W = (int)rho - 2;
+  s.pathr = 0; s.anom = 0; s.e = 0; s.c = 0; s.viol = 0;
+  uint32_t unused = 0;
+  for (uint32_t j = first_deep; j <= q; ++j)
+    top_down_level<false, false>(pm1, q, j, s, unused, [](uint32_t, int) {});
+  uint32_t lv_lo = 0, lv_hi = 0, n_out = 0;
+  bool all_deep = true;
+  auto note = [&](uint32_t k, int val) {
+    const uint32_t level = (uint32_t)(-val);
+    all_deep = all_deep && val < 0 && level >= first_deep && level - first_deep < 16u && k == n_out;
+    const uint32_t nib = (level - first_deep) & 15u;
+    if (k < 8u) lv_lo |= nib << (4u * k);
+    else if (k < 16u) lv_hi |= nib << (4u * (k - 8u));
+    ++n_out;
+  };
+  AscentState a = ascent_start(pm1, q, s.jb, s.W, s.pathr, note);
+  bool anomaly = false;
+  LockstepCache none;
+  lockstep_cache_init(none, nullptr);
+  ascent_run<true>(pm1, q, s.jb, q - 1u, a, s.anom, anomaly, note, none, false);
+  const uint32_t live_deep = a.live >> first_deep;
+  const bool ok = !anomaly && all_deep && s.rem == 0u && s.jb >= first_deep && s.jb - first_deep < 16u &&
+                  a.pathr == 0u && (int)a.j < 0 && a.k == n_out && a.k <= 11u && a.k < q &&
+                  live_deep < 2048u && a.D < 65536u && a.M < 65536u &&
+                  (a.live & ((1u << first_deep) - 1u)) == ((1u << first_deep) - 1u);
+  if (!ok) return e;
+  e.x = live_deep | ((s.jb - first_deep) << 11) | (a.k << 15) | 0x80000000u;
+  e.y = a.D | (a.M << 16);
+  e.z = lv_lo; e.w = lv_hi;
+  return e;
+}
+
 // Phase one of a rank: baseblock, receive schedule, send walk.  Writes
 // recvblock[k] to recv_row[k] and sendblock[k] to send_row[k] (bytes), returns
 // the mask of violation rounds still to be filled in, the baseblock and flags.
 // `cache` is the wavefront's lockstep record; use_cache may be true only when
 // all 64 lanes make this call together (a full tile).
+//
+// kMemo: the deep levels come from the table of deep entries (see DeepTable) wherever the rank
+// has an entry, and the levels above them are all recorded and taken over together.  `room` then
+// says how far above v the ranks still make the same decisions at the levels above the deep ones
+// (their rho is rho(v) plus the distance), which is what answering a violation from the table
+// needs; `rho` is v's own.
+struct MemoOut {
+  uint32_t rho, room;
+};
+
+template <bool kMemo>
 __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
                                                         int8_t *recv_row, int8_t *send_row,
                                                         int &b_out, uint32_t &flags,
-                                                        LockstepCache &cache, bool use_cache) {
+                                                        LockstepCache &cache, bool use_cache,
+                                                        const DeepTable &table, MemoOut &memo) {
   const uint32_t q = in.q;
   flags = 0;
   b_out = 0;
+  memo.rho = 0; memo.room = 0;
   if (q == 0) return 0;
   auto put_send = [&](uint32_t k, int val) { send_row[k] = (int8_t)val; };
+  auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
   TopDown s = top_down_start(in.p, v);
   // the root and rank 1 start differently: their tile runs without the record
   const bool use = use_cache && !__any(v <= 1u);
@@ -539,12 +663,16 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   // (if it is indeed the same in all lanes) and how far v may move before any test flips; a
   // later tile whose ranks are closer than that takes the state over.  Its rows still hold
   // the top rounds of Algorithm 6 from the recording tile, which are what it would write.
-  const uint32_t n_top = use ? top_level_count(in.pm1, q) : 0u;
+  const uint32_t n_upper = kMemo ? table.first_deep - 1u : 0u;     // levels above the deep ones
+  const uint32_t n_top = kMemo ? (use ? n_upper : 0u) : (use ? top_level_count(in.pm1, q) : 0u);
+  uint32_t margin_own = 0xFFFFFFFFu;         // kMemo: flip distance of this lane's own tests
+  bool took_over = false;
   if (n_top >= 4u) {
     const uint32_t dv = v - cache.top_v;
     const uint32_t dv0 = lane0_of(dv);
+    const uint32_t away = flip_distance(v, cache.top_v);
     const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == dv0 &&
-                      flip_distance(v, cache.top_v) + 1u <= cache.mem[kTopMargin];
+                      away + 1u <= cache.mem[kTopMargin];
     if (!__any(!near)) {
       s.rem = v - cache.mem[kTopT];
       s.W = (int)(v - cache.mem[kTopTw]);
@@ -553,6 +681,8 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       s.closed = (cache.mem[kTopBits] & 1u) != 0u;
       s.anom = cache.mem[kTopBits] >> 1;
       cache.mem[kTopReplays] = cache.mem[kTopReplays] + 1u;
+      took_over = true;
+      if (kMemo) margin_own = cache.mem[kTopMargin] - away;     // >= 1: what is left of the margin
     } else {
       uint32_t margin = 0xFFFFFFFFu;
       for (; j <= n_top; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
@@ -572,10 +702,56 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       cache.mem[kTopC] = c0; cache.mem[kTopViol] = viol0;
       cache.mem[kTopBits] = bits0;
       cache.mem[kTopMargin] = wave_min32(margin);
+      margin_own = margin;
     }
     j = n_top + 1u;
   }
-  for (; j <= q; ++j) top_down_level<true, false>(in.pm1, q, j, s, unused, put_send);
+  bool anomaly = false;
+  uint32_t produced;
+  if (!kMemo) {
+    for (; j <= q; ++j) top_down_level<true, false>(in.pm1, q, j, s, unused, put_send);
+  } else {
+    // levels above the deep ones that no record covers (short runs, partial tiles, the first
+    // ranks): one by one, keeping track of how far the decisions hold
+    if (!took_over && j <= n_upper) {
+      uint32_t margin = 0xFFFFFFFFu;
+      for (; j <= n_upper; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
+      margin_own = margin;
+    }
+    j = n_upper + 1u;
+    const uint32_t rho = s.rem;
+    memo.rho = rho;
+    memo.room = margin_own - 1u;                       // margin_own >= 1 (0 only if a test sat on its edge)
+    memo.room = margin_own == 0u ? 0u : memo.room;
+    bool generic = rho >= 2u && rho < table.n_rho && (uint32_t)s.W == rho - 2u && !s.closed;
+    uint4 e;
+    e.x = 0; e.y = 0; e.z = 0; e.w = 0;
+    if (generic) e = table.entries[rho];
+    generic = generic && (e.x >> 31) != 0u;
+    AscentState a;
+    if (generic) {
+      // Algorithm 6 goes through the deep levels as ever (its e and c are the rank's own); the
+      // descent and Algorithm 3's baseblock come from the entry
+      for (; j <= q; ++j) top_down_level<true, false, false>(in.pm1, q, j, s, unused, put_send);
+      const uint32_t fd = table.first_deep;
+      s.jb = fd + ((e.x >> 11) & 15u);
+      const uint32_t n_acc = (e.x >> 15) & 15u;
+      for (uint32_t k = 0; k < n_acc; ++k) {
+        const uint32_t nib = k < 8u ? (e.z >> (4u * k)) & 15u : (e.w >> (4u * (k - 8u))) & 15u;
+        recv_row[k] = (int8_t)(-(int)(fd + nib));
+      }
+      a.D = e.y & 0xFFFFu; a.M = e.y >> 16;
+      a.k = n_acc;
+      a.sk1 = skip_at_level(in.pm1, (q - n_acc - 1u) & 31u);    // skip[K + 1]; K < q
+      a.j = kEndLevel;
+      a.live = ((1u << fd) - 1u) | ((e.x & 0x7FFu) << fd);
+      a.pathr = s.pathr;
+    } else {
+      for (; j <= q; ++j) top_down_level<true, false>(in.pm1, q, j, s, unused, put_send);
+      a = ascent_start(in.pm1, q, s.jb, s.W, s.pathr, put_recv);
+    }
+    produced = ascent_run<false>(in.pm1, q, s.jb, q - 1u, a, s.anom, anomaly, put_recv, cache, use);
+  }
   const uint32_t jb = s.jb;
   const int b = (int)q - (int)jb;
   b_out = b;
@@ -589,14 +765,51 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
     for (uint32_t j = 1; j < jt; ++j) send_row[q - j] = (int8_t)b;
     send_row[0] = (int8_t)(b - (int)q);
   }
-  bool anomaly = false;
-  uint32_t produced;
-  auto put_recv = [&](uint32_t k, int val) { recv_row[k] = (int8_t)val; };
-  produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
-                         cache, use);
+  if (!kMemo)
+    produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
+                           cache, use);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
   if (__popc(viol) > 4) flags |= BCAST_F_VIOLATIONS;
   return viol;
+}
+
+// Without the table of deep entries.
+__device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
+                                                        int8_t *recv_row, int8_t *send_row,
+                                                        int &b_out, uint32_t &flags,
+                                                        LockstepCache &cache, bool use_cache) {
+  DeepTable none;
+  none.entries = nullptr; none.first_deep = 0; none.n_rho = 0;
+  MemoOut unused;
+  return compute_rank_phase1<false>(in, v, recv_row, send_row, b_out, flags, cache, use_cache, none, unused);
+}
+
+// A violation of Algorithm 6 in round k answered from the table of deep entries: the
+// to-processor t = v + skip[k] makes the same decisions as v at the levels above the deep ones
+// (skip[k] <= room), so its rho is rho(v) + skip[k], and recvblock[k] of t is in its entry if the
+// entry reaches round k.  Returns the violations that are still open.
+__device__ __forceinline__ uint32_t resolve_from_table(const Instance &in, const DeepTable &table,
+                                                       uint32_t v, const MemoOut &memo,
+                                                       uint32_t viol, int8_t *send_row) {
+  uint32_t open = 0;
+  while (viol != 0) {
+    const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
+    viol &= viol - 1u;
+    const uint32_t sk = skip_at_level(in.pm1, in.q - k);
+    const uint32_t rho_t = memo.rho + sk;
+    bool done = false;
+    if (sk <= memo.room && rho_t < table.n_rho && rho_t >= 2u && v + sk < in.p && k < 12u) {
+      const uint4 e = table.entries[rho_t];
+      const uint32_t n_acc = (e.x >> 15) & 15u;
+      if ((e.x >> 31) != 0u && k < n_acc) {
+        const uint32_t nib = k < 8u ? (e.z >> (4u * k)) & 15u : (e.w >> (4u * (k - 8u))) & 15u;
+        send_row[k] = (int8_t)(-(int)(table.first_deep + nib));
+        done = true;
+      }
+    }
+    if (!done) open |= 1u << k;
+  }
+  return open;
 }
 
 // Phase two, for tiles of consecutive ranks: a violation in round k needs

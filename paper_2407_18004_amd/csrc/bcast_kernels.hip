@@ -98,6 +98,7 @@ struct SchedParams {
   int32_t *recv, *send;
   int64_t ld;
   int layout;
+  DeepTable table;                  // kernels with kMemo only
 };
 
 // The run of wavefront `wave` (the same in all lanes) of this workgroup: first tile and number
@@ -142,11 +143,13 @@ struct TileState {
 // violations of Algorithm 6 resolved from rows of the same tile or else by
 // search on the spot: for p = 2^q and 2^q - 1, which have next to none.
 // slices: the workgroup's four slices, slice_w words each.
+template <bool kMemo>
 __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_begin,
                                                uint64_t n_ranks, uint64_t tile, uint64_t n_tiles,
                                                uint32_t *slices, uint32_t slice_w, uint32_t pitch,
                                                uint32_t send_off, uint32_t lane, uint32_t wave,
-                                               LockstepCache &cache, bool use_cache) {
+                                               LockstepCache &cache, bool use_cache,
+                                               const DeepTable &table) {
   TileState st;
   st.v = 0; st.flags = 0; st.b = 0;
   int8_t *tile_recv = reinterpret_cast<int8_t *>(slices + wave * slice_w);
@@ -155,15 +158,18 @@ __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_be
   const uint64_t row0 = tile * kWave;
   st.n_valid = tile < n_tiles ? (n_ranks - row0 < kWave ? (uint32_t)(n_ranks - row0) : kWave) : 0u;
   uint32_t viol = 0;
+  MemoOut memo;
+  memo.rho = 0; memo.room = 0;
   if (lane < st.n_valid) {
     st.v = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
-    viol = compute_rank_phase1(in, st.v, recv_row, send_row, st.b, st.flags,
-                               cache, use_cache && st.n_valid == (uint32_t)kWave);
+    viol = compute_rank_phase1<kMemo>(in, st.v, recv_row, send_row, st.b, st.flags,
+                                      cache, use_cache && st.n_valid == (uint32_t)kWave, table, memo);
   }
   wave_lds_sync();
   if (lane < st.n_valid) {
-    const uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, nullptr, pitch, pitch,
-                                             lane, st.n_valid, 0u);
+    uint32_t open = resolve_from_tiles(in, viol, send_row, tile_recv, nullptr, pitch, pitch,
+                                       lane, st.n_valid, 0u);
+    if (kMemo) open = resolve_from_table(in, table, st.v, memo, open, send_row);
     st.flags |= resolve_by_search(in, st.v, open, send_row);
   }
   wave_lds_sync();
@@ -207,7 +213,7 @@ __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedPa
   }
 }
 
-template <bool kShare>
+template <bool kShare, bool kMemo>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_schedules(SchedParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -244,8 +250,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   if (!kShare) {
     lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
-      const TileState st = tile_rows(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
-                                     pitch, send_off, lane, wave, record, long_run);
+      const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
+                                            pitch, send_off, lane, wave, record, long_run, prm.table);
       copy_out(tile * kWave, st.n_valid);
       wave_lds_sync();                         // the slice is rewritten next
     }
@@ -263,16 +269,20 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     const uint32_t n_valid = prm.n_ranks - row0 < kWave ? (uint32_t)(prm.n_ranks - row0) : kWave;
     uint32_t v = 0, viol = 0, flags = 0;
     int b = 0;
+    MemoOut memo;
+    memo.rho = 0; memo.room = 0;
     if (lane < n_valid) {
       v = virtual_rank(in, (uint32_t)(prm.r_begin + row0 + lane));
-      viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags,
-                                 record, long_run && n_valid == (uint32_t)kWave);
+      viol = compute_rank_phase1<kMemo>(in, v, recv_row, send_row, b, flags,
+                                        record, long_run && n_valid == (uint32_t)kWave, prm.table, memo);
     }
     wave_lds_sync();
     uint32_t open = 0;
-    if (lane < n_valid)
+    if (lane < n_valid) {
       open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                 pitch, q, lane, n_valid, n_valid_above);
+      if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
+    }
     // Open violations go into the queue as (row within the run) << 5 | k.  A tile can have more
     // of them than the queue has room for: then the rows leave first, a batch of 64 entries is
     // filled in (their rows are in the table by then), and the rest is queued after that.
@@ -374,6 +384,7 @@ struct DigestParams {
   RunSplit runs;
   uint64_t *digest;
   uint32_t *flags;
+  DeepTable table;                  // kernels with kMemo only
 };
 
 __global__ void k_digest_init(uint64_t *digest, uint32_t *flags) {
@@ -395,7 +406,7 @@ __global__ void k_edges_init(uint64_t *xors) {
 // each lane computes one such rank again from scratch, violations by search,
 // and hashes it.  That is 2 to 3 ranks in 64; it costs the slice its rows, so
 // the record of the top levels starts again after a batch.
-template <bool kShare, bool kEdges>
+template <bool kShare, bool kEdges, bool kMemo>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -429,8 +440,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   if (!kShare) {
     lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
-      const TileState st = tile_rows(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
-                                     2u * q, q, lane, wave, record, long_run);
+      const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
+                                            2u * q, q, lane, wave, record, long_run, prm.table);
       acc_flags |= st.flags;
       if (lane < st.n_valid) take_row((uint32_t)(prm.r_begin + tile * kWave + lane), st.v, st.b);
       wave_lds_sync();                         // the slice is rewritten next
@@ -462,10 +473,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       const uint32_t r = (uint32_t)(prm.r_begin + row);
       uint32_t v = 0, viol = 0, flags = 0;
       int b = 0;
+      MemoOut memo;
+      memo.rho = 0; memo.room = 0;
       if (lane < n_here) {
         v = virtual_rank(in, r);
-        viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags, record,
-                                   !batch && long_run && n_here == (uint32_t)kWave);
+        viol = compute_rank_phase1<kMemo>(in, v, recv_row, send_row, b, flags, record,
+                                          !batch && long_run && n_here == (uint32_t)kWave, prm.table, memo);
       }
       acc_flags |= flags;
       wave_lds_sync();
@@ -476,6 +489,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         } else {
           open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                     2u * q, q, lane, n_here, n_valid_above);
+          if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
         }
         if (open == 0) take_row(r, v, b);
       }
@@ -506,6 +520,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
     else if (acc_flags) atomicOr(prm.flags, acc_flags);
   }
+}
+
+// ------------------------------------------------- table of deep entries
+
+// One lane per rho (see DeepTable in the device header).
+__global__ __launch_bounds__(kBlock) void k_deep_table(uint4 *entries, uint32_t p, uint32_t q,
+                                                       uint32_t first_deep, uint32_t n_rho) {
+  const uint32_t rho = blockIdx.x * kBlock + threadIdx.x;
+  if (rho < n_rho) entries[rho] = deep_entry_build(p - 1u, q, first_deep, rho);
 }
 
 // ----------------------------------------------------------------- doubling
@@ -1126,8 +1149,45 @@ int bcast_skips(uint32_t p, uint32_t *skips, int *q_out) {
   return BCAST_OK;
 }
 
-int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
-                    int32_t *recv, int32_t *send, int64_t ld, void *stream) {
+// Bytes of the workspace of the *_ws calls: the table of deep entries.
+size_t bcast_schedules_workspace(uint32_t p) {
+  if (host_q(p) < 0) return 0;
+  return (size_t)kDeepMaxEntries * sizeof(uint4) + 256u;
+}
+
+}  // extern "C"
+
+namespace {
+
+// The table of deep entries of p in the caller's workspace (built on the stream, before the
+// kernel that reads it), or none: no workspace, or p has too few levels above the deep ones.
+// Returns false when a launch failed.
+// Building the table takes one small kernel ahead of the main one, some 15 us from launch to end;
+// it pays from a few million ranks on (measured on MI355X: tables of 2^23 ranks 1.4 times
+// faster, p = 1,000,003 10 % slower), so shorter ranges are computed without it.
+constexpr uint64_t kTableMinRanks = 1ull << 21;
+
+bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStream_t st, DeepTable &table) {
+  table.entries = nullptr; table.first_deep = 0; table.n_rho = 0;
+  if (!workspace || q <= 0 || n_ranks < kTableMinRanks) return true;
+  uint32_t first_deep = 0;                         // as first_deep_level() on the device
+  if (p - 1u >= kLockstepSkip) {
+    uint32_t x = (p - 1u) / kLockstepSkip;
+    while (x) { ++first_deep; x >>= 1; }
+  }
+  if (first_deep < kDeepMinUpperLevels + 1u) return true;
+  const uint32_t n_rho = ((p - 1u) >> (first_deep - 1u)) + 1u;      // smallest skip above the deep levels
+  if (n_rho > kDeepMaxEntries) return true;
+  uint4 *entries = reinterpret_cast<uint4 *>(align_up(reinterpret_cast<uintptr_t>(workspace), 256));
+  hipLaunchKernelGGL(k_deep_table, dim3((n_rho + kBlock - 1) / kBlock), dim3(kBlock), 0, st, entries, p,
+                     (uint32_t)q, first_deep, n_rho);
+  if (!launch_ok()) return false;
+  table.entries = entries; table.first_deep = first_deep; table.n_rho = n_rho;
+  return true;
+}
+
+int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, int32_t *recv,
+                   int32_t *send, int64_t ld, void *workspace, void *stream) {
   const int q = host_q(p);
   if (q < 0 || root >= p || r_begin > r_end || r_end > p) return BCAST_EINVAL;
   const uint64_t n = r_end - r_begin;
@@ -1152,77 +1212,115 @@ int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
     prm.layout = kRowwise;
   }
   const uint64_t blocks = (n + kBlock - 1) / kBlock;
-  if (keep_next_tile(p)) {
-    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
-    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    hipLaunchKernelGGL(k_schedules<true>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+  const bool share = keep_next_tile(p);
+  const int grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : persistent_grid(blocks);
+  if (grid < 0) return BCAST_EHIP;
+  prm.runs = split_runs((n + kWave - 1) / kWave, grid);
+  if (!prepare_table(p, q, n, workspace, (hipStream_t)stream, prm.table)) return BCAST_EHIP;
+  const bool memo = prm.table.entries != nullptr;
+  const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
+                           : (size_t)lone_block_words(prm.q) * 4u;
+  if (share) {
+    if (memo) hipLaunchKernelGGL((k_schedules<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    else hipLaunchKernelGGL((k_schedules<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   } else {
-    const int grid = persistent_grid(blocks);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
-    hipLaunchKernelGGL(k_schedules<false>, dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    if (memo) hipLaunchKernelGGL((k_schedules<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    else hipLaunchKernelGGL((k_schedules<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+// digest and flags (edges = false) or the two sums of the edge check (edges = true, into out64)
+int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                uint64_t *out64, uint32_t *flags, void *workspace, void *stream) {
+  const int q = host_q(p);
+  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !out64 || (!edges && !flags))
+    return BCAST_EINVAL;
+  const uint64_t n = r_end - r_begin;
+  const bool share = keep_next_tile(p);
+  const bool work = n != 0 && !(edges && q == 0);
+  int grid = 1;
+  if (work) {
+    grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : persistent_grid((n + kBlock - 1) / kBlock);
+    if (grid < 0) return BCAST_EHIP;
+  } else if (persistent_grid(1) < 0) {
+    return BCAST_EHIP;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  if (edges) hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, st, out64);
+  else hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, st, out64, flags);
+  if (!launch_ok()) return BCAST_EHIP;
+  if (!work) return BCAST_OK;
+  DigestParams prm;
+  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
+  prm.r_begin = r_begin; prm.n_ranks = n;
+  prm.digest = out64; prm.flags = edges ? nullptr : flags;
+  prm.runs = split_runs((n + kWave - 1) / kWave, grid);
+  if (!prepare_table(p, q, n, workspace, st, prm.table)) return BCAST_EHIP;
+  const bool memo = prm.table.entries != nullptr;
+  const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
+                           : (size_t)lone_block_words(prm.q) * 4u;
+  const dim3 g(grid), b(kBlock);
+#define BCAST_LAUNCH_DIGEST(S, E, M) hipLaunchKernelGGL((k_digest<S, E, M>), g, b, lds, st, prm)
+  if (share) {
+    if (edges) { if (memo) BCAST_LAUNCH_DIGEST(true, true, true); else BCAST_LAUNCH_DIGEST(true, true, false); }
+    else { if (memo) BCAST_LAUNCH_DIGEST(true, false, true); else BCAST_LAUNCH_DIGEST(true, false, false); }
+  } else {
+    if (edges) { if (memo) BCAST_LAUNCH_DIGEST(false, true, true); else BCAST_LAUNCH_DIGEST(false, true, false); }
+    else { if (memo) BCAST_LAUNCH_DIGEST(false, false, true); else BCAST_LAUNCH_DIGEST(false, false, false); }
+  }
+#undef BCAST_LAUNCH_DIGEST
+  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+}
+
+// workspace argument of a *_ws call: NULL is an error there, and so is one that is too small
+int check_workspace(uint32_t p, const void *workspace, size_t workspace_bytes) {
+  const size_t need = bcast_schedules_workspace(p);
+  if (need == 0 || !workspace) return BCAST_EINVAL;
+  return workspace_bytes < need ? BCAST_ENOMEM : BCAST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                    int32_t *recv, int32_t *send, int64_t ld, void *stream) {
+  return schedules_impl(p, root, r_begin, r_end, recv, send, ld, nullptr, stream);
+}
+
+int bcast_schedules_ws(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                       int32_t *recv, int32_t *send, int64_t ld, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+  const int rc = check_workspace(p, workspace, workspace_bytes);
+  if (rc != BCAST_OK) return rc;
+  return schedules_impl(p, root, r_begin, r_end, recv, send, ld, workspace, stream);
 }
 
 int bcast_schedules_digest(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
                            uint64_t *digest, uint32_t *flags, void *stream) {
-  const int q = host_q(p);
-  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !digest || !flags)
-    return BCAST_EINVAL;
-  hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, (hipStream_t)stream, digest, flags);
-  if (!launch_ok()) return BCAST_EHIP;
-  const uint64_t n = r_end - r_begin;
-  if (n == 0) return BCAST_OK;
-  DigestParams prm;
-  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
-  prm.r_begin = r_begin; prm.n_ranks = n;
-  prm.digest = digest; prm.flags = flags;
-  if (keep_next_tile(p)) {
-    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
-    hipLaunchKernelGGL((k_digest<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
-  } else {
-    const int grid = persistent_grid((n + kBlock - 1) / kBlock);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
-    hipLaunchKernelGGL((k_digest<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
-  }
-  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+  return digest_impl(false, p, root, r_begin, r_end, digest, flags, nullptr, stream);
+}
+
+int bcast_schedules_digest_ws(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                              uint64_t *digest, uint32_t *flags, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+  const int rc = check_workspace(p, workspace, workspace_bytes);
+  if (rc != BCAST_OK) return rc;
+  return digest_impl(false, p, root, r_begin, r_end, digest, flags, workspace, stream);
 }
 
 int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
                               uint64_t *xors, void *stream) {
-  const int q = host_q(p);
-  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !xors) return BCAST_EINVAL;
-  hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, (hipStream_t)stream, xors);
-  if (!launch_ok()) return BCAST_EHIP;
-  const uint64_t n = r_end - r_begin;
-  if (n == 0 || q == 0) return BCAST_OK;
-  DigestParams prm;
-  prm.p = p; prm.q = (uint32_t)q; prm.root = root;
-  prm.r_begin = r_begin; prm.n_ranks = n;
-  prm.digest = xors; prm.flags = nullptr;
-  if (keep_next_tile(p)) {
-    const int grid = run_grid((n + kWave - 1) / kWave, 8u);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    const size_t lds = (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u;
-    hipLaunchKernelGGL((k_digest<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
-  } else {
-    const int grid = persistent_grid((n + kBlock - 1) / kBlock);
-    if (grid < 0) return BCAST_EHIP;
-    prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-    const size_t lds = (size_t)lone_block_words(prm.q) * 4u;
-    hipLaunchKernelGGL((k_digest<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
-  }
-  return launch_ok() ? BCAST_OK : BCAST_EHIP;
+  return digest_impl(true, p, root, r_begin, r_end, xors, nullptr, nullptr, stream);
+}
+
+int bcast_schedules_edgecheck_ws(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                                 uint64_t *xors, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+  const int rc = check_workspace(p, workspace, workspace_bytes);
+  if (rc != BCAST_OK) return rc;
+  return digest_impl(true, p, root, r_begin, r_end, xors, nullptr, workspace, stream);
 }
 
 int bcast_schedules_double(uint32_t p, const int32_t *in, int32_t *out, void *stream) {

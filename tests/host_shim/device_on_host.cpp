@@ -112,7 +112,7 @@ static uint32_t q_of(uint32_t p) {
   return q;
 }
 
-static uint64_t g_replays = 0, g_top_replays = 0;
+static uint64_t g_replays = 0, g_top_replays = 0, g_from_table = 0, g_generic = 0;
 
 extern "C" {
 
@@ -151,13 +151,27 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
 // 2^q - 1).  Phase one of a tile runs as a wavefront of 64 lanes (shim_wave::run) with one
 // record shared by the lanes, as in LDS; then violations are filled in from rows of the same
 // tile or the tile above, then the rest by search.
+// use_table != 0: with the table of deep entries (built here, one entry per rho, by the
+// function the GPU's builder kernel calls), when p has enough levels above the deep ones.
 int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n,
-                         uint32_t run_tiles, int descending,
+                         uint32_t run_tiles, int descending, int use_table,
                          int32_t *rows, uint32_t *flags_out, uint64_t *hash_out,
                          uint64_t *n_from_tile) {
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
   uint64_t borrowed = 0;
+  static uint4 entries[kDeepMaxEntries];
+  DeepTable table;
+  table.entries = nullptr; table.first_deep = 0; table.n_rho = 0;
+  g_from_table = 0; g_generic = 0;
+  if (use_table && q > 0 && first_deep_level(p - 1u) >= kDeepMinUpperLevels + 1u) {
+    table.first_deep = first_deep_level(p - 1u);
+    table.n_rho = deep_table_rhos(p - 1u, table.first_deep);
+    if (table.n_rho > kDeepMaxEntries) return -1;
+    for (uint32_t rho = 0; rho < table.n_rho; ++rho)
+      entries[rho] = deep_entry_build(p - 1u, q, table.first_deep, rho);
+    table.entries = entries;
+  }
   // one slice that is reused (rows of the previous tile stay where they are until they are
   // overwritten) and a copy of the receive rows of the tile above
   static int8_t tile[64 * 62];
@@ -183,17 +197,29 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
       const uint32_t n_valid = n - row0 < 64 ? (uint32_t)(n - row0) : 64u;
       uint32_t viol[64], fl[64], vr[64];
       int b[64];
+      MemoOut memo[64];
       shim_wave::run((int)n_valid, [&](int lane) {
         vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
-        viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
-                                         tile + lane * 2 * q + q, b[lane], fl[lane],
-                                         caches[lane], long_run && n_valid == 64);
+        if (table.entries)
+          viol[lane] = compute_rank_phase1<true>(in, vr[lane], tile + lane * 2 * q,
+                                                 tile + lane * 2 * q + q, b[lane], fl[lane],
+                                                 caches[lane], long_run && n_valid == 64, table, memo[lane]);
+        else
+          viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
+                                           tile + lane * 2 * q + q, b[lane], fl[lane],
+                                           caches[lane], long_run && n_valid == 64);
       });
       for (uint32_t lane = 0; lane < n_valid; ++lane) {
         int8_t *recv_row = tile + lane * 2 * q;
-        const uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
-                                                 2 * q, q, lane, n_valid, n_valid_next);
+        uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
+                                           2 * q, q, lane, n_valid, n_valid_next);
         borrowed += (uint64_t)__popc(viol[lane] ^ open);
+        if (table.entries) {
+          const uint32_t left = resolve_from_table(in, table, vr[lane], memo[lane], open, recv_row + q);
+          g_from_table += (uint64_t)__popc(open ^ left);
+          g_generic += memo[lane].rho >= 2u;
+          open = left;
+        }
         fl[lane] |= resolve_by_search(in, vr[lane], open, recv_row + q);
       }
       for (uint32_t lane = 0; lane < n_valid; ++lane) {
@@ -217,6 +243,25 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   }
   if (n_from_tile) *n_from_tile = borrowed;
   return (int)q;
+}
+
+// violations of the last shim_schedules_tiles call answered from the table of deep entries, and
+// ranks that had a rho of 2 or more
+uint64_t shim_last_from_table(void) { return g_from_table; }
+uint64_t shim_last_generic(void) { return g_generic; }
+
+// the table of deep entries of p (n entries of four words), as the builder kernel writes it
+int shim_deep_table(uint32_t p, uint32_t *out, uint32_t cap) {
+  const uint32_t q = q_of(p);
+  if (q == 0) return 0;
+  const uint32_t fd = first_deep_level(p - 1u);
+  const uint32_t n = deep_table_rhos(p - 1u, fd);
+  if (n > cap) return -1;
+  for (uint32_t rho = 0; rho < n; ++rho) {
+    const uint4 e = deep_entry_build(p - 1u, q, fd, rho);
+    out[4 * rho] = e.x; out[4 * rho + 1] = e.y; out[4 * rho + 2] = e.z; out[4 * rho + 3] = e.w;
+  }
+  return (int)n;
 }
 
 // cross-lane operations carried out by the last shim_schedules_tiles call, and how many of them

@@ -14,6 +14,8 @@
 #define __forceinline__ inline
 #define __host__
 
+struct uint4 { unsigned x, y, z, w; };
+
 static inline int __ffs(int x) { return x == 0 ? 0 : __builtin_ctz((unsigned)x) + 1; }
 static inline int __clz(int x) { return x == 0 ? 32 : __builtin_clz((unsigned)x); }
 static inline int __popc(unsigned x) { return __builtin_popcount(x); }

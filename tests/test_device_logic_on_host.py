@@ -35,10 +35,12 @@ def shim():
                                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_edge_row.restype = None
     lib.shim_schedules_tiles.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
-                                         ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int,
+                                         ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_last_replays.restype = ctypes.c_uint64
+    lib.shim_last_from_table.restype = ctypes.c_uint64
+    lib.shim_last_generic.restype = ctypes.c_uint64
     lib.shim_wave_operations.restype = ctypes.c_uint64
     lib.shim_wave_mismatches.restype = ctypes.c_uint64
     lib.shim_recv_two_ways.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
@@ -61,7 +63,7 @@ def shim_rows(lib, p, root, ranks):
     return rows, flags, hashes
 
 
-def shim_tiles(lib, p, root, r_begin, n, run_tiles=0, descending=True):
+def shim_tiles(lib, p, root, r_begin, n, run_tiles=0, descending=True, use_table=False):
     """Rows, flags and hashes of n consecutive ranks, computed tile by tile by a wavefront of 64
     lanes on the CPU (runs of run_tiles tiles; 0 = one run), and the violations of Algorithm 6
     that were answered from a neighbour's row."""
@@ -70,7 +72,7 @@ def shim_tiles(lib, p, root, r_begin, n, run_tiles=0, descending=True):
     flags = np.zeros(n, dtype=np.uint32)
     hashes = np.zeros(n, dtype=np.uint64)
     borrowed = ctypes.c_uint64(0)
-    lib.shim_schedules_tiles(p, root, r_begin, n, run_tiles, int(descending),
+    lib.shim_schedules_tiles(p, root, r_begin, n, run_tiles, int(descending), int(use_table),
                              rows.ctypes.data if rows.size else None,
                              flags.ctypes.data, hashes.ctypes.data, ctypes.byref(borrowed))
     assert int(lib.shim_wave_mismatches()) == 0       # the lanes met at the same operations
@@ -186,6 +188,39 @@ def test_replayed_lockstep_stretch_equals_the_search(shim):
                 assert replays_here > n // 64 // 4, (p, replays_here)     # the record is actually used
                 assert top_here > n // 64 // 4, (p, top_here)
     assert replays > 10000
+
+
+def test_table_of_deep_entries_equals_the_search(shim):
+    # With the table of deep entries a rank takes its baseblock, its first receive entries and the
+    # state of the search after them from the entry of its rho, and violations of Algorithm 6
+    # are answered from the to-processor's entry.  Everything must still equal Algorithms 5 and 6
+    # of the oracle: all ranks of several p (small enough for that), and long stretches at both
+    # ends, around powers of two and across the root for large p, in runs like the kernels'.
+    from_table = generic = ranks = 0
+    whole = [16385, 20000, 32767, 32768, 32769, 65537, 100003, 131071]
+    cases = [(p, r, 0, p) for p in whole for r in (0, p // 3)]
+    cases += [(2**31 - 1, 0, 2**30 - 30000, 60000), (2**31 - 1, 12345, 2**31 - 1 - 50000, 50000),
+              (2**31 - 1, 0, 0, 40000), (1000003, 0, 0, 150000), (1000003, 999999, 860000, 140003),
+              (805306373, 7, 402653000, 50000), (2**30 + 1, 2**29, 2**29 - 20000, 40000),
+              (3 * 2**20, 5, 2**20 - 10000, 30000), (2**30, 2**29 + 7, 2**29 - 20000, 45000),
+              (2**27 - 1, 5, 2**26 - 25000, 50001), (2**24 + 1, 0, 2**24 - 40000, 40001),
+              (16384 * 3 + 1, 0, 0, 16384 * 3 + 1)]
+    for p, root, a, n in cases:
+        want = oracle.schedules(p, root=root, r_begin=a, r_end=a + n, send_mode=1)
+        for run_tiles, descending in [(0, True), (6, True), (4, False), (2, True)]:
+            rows, flags, hashes, _ = shim_tiles(shim, p, root, a, n, run_tiles, descending, use_table=True)
+            assert np.array_equal(rows, want), (p, root, a, n, run_tiles, descending)
+            assert not flags.any()
+            from_table += int(shim.shim_last_from_table())
+            generic += int(shim.shim_last_generic())
+            ranks += n
+        dg, fl = oracle.digest(p, root, a, a + n)
+        assert int(np.bitwise_xor.reduce(hashes)) == dg and fl == 0
+    assert generic > 0.99 * ranks                   # nearly every rank has an entry
+    assert from_table > 100000                      # and violations are answered from the table
+    # small p has no levels above the deep ones: the table is not used, the result is the same
+    rows, flags, _, _ = shim_tiles(shim, 4099, 5, 0, 4099, 0, True, use_table=True)
+    assert np.array_equal(rows, oracle.schedules(4099, root=5)) and int(shim.shim_last_generic()) == 0
 
 
 def test_level_helpers_against_the_skips(shim):

@@ -702,3 +702,104 @@ def test_baseblock_listing_in_linear_time():
         assert np.array_equal(got, want), lo
         for x in rng.integers(lo, lo + 2**20, size=8):
             assert got[int(x) - lo] == oracle.baseblock(p, int(x))
+
+
+# --------------------------------------- the calls with a workspace (table of deep entries) --
+
+def ws_table(p, root, a, b, ws=None):
+    q = lib.bcast_q(p)
+    if ws is None:
+        ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+    t = torch.full((max(b - a, 0), 2 * q), 99, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules_ws(p, root, a, b, t, t, 2 * q, ws, send_offset=q)
+    torch.cuda.synchronize()
+    return t
+
+
+def ws_digest_and_edges(p, root, a, b, ws):
+    dg = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    fl = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    x = torch.full((2,), -1, dtype=torch.int64, device=DEV)
+    lib.bcast_schedules_digest_ws(p, root, a, b, dg, fl, ws)
+    lib.bcast_schedules_edgecheck_ws(p, root, a, b, x, ws)
+    torch.cuda.synchronize()
+    xr, xs = (int(t) & oracle.U64_MAX for t in x.cpu().tolist())
+    return (int(dg.item()) & oracle.U64_MAX, int(fl.item()) & 0xFFFFFFFF), (xr, xs)
+
+
+@pytest.mark.parametrize("p,root,a,n", [
+    (4000037, 123457, 1000, 2_400_000),       # few violations per rank
+    (2**22 + 1, 0, 0, 2**22 + 1),             # more than one violation per rank, all ranks
+    (2**22 + 1, 2**22, 5, 2**22 - 100),
+    (2**23 - 1, 3, 0, 2**23 - 1),             # the kernels whose wavefronts work alone
+    (2**24, 2**23 + 5, 2**23 - 2_000_000, 4_000_001),
+    (3 * 2**20 + 1, 77, 0, 3 * 2**20 + 1),    # the smallest skip above the deep levels is odd
+    (1000003, 0, 0, 1000003), (20000, 1, 0, 20000), (100, 3, 0, 100), (1, 0, 0, 1),   # below the thresholds
+])
+def test_calls_with_workspace_equal_the_oracle(p, root, a, n):
+    b = a + n
+    ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+    want = oracle.schedules(p, root=root, r_begin=a, r_end=b, send_mode=1)
+    assert np.array_equal(ws_table(p, root, a, b, ws).cpu().numpy(), want)
+    dg, xs = ws_digest_and_edges(p, root, a, b, ws)
+    assert dg == oracle.digest(p, root, a, b, send_mode=1)
+    assert xs == oracle.edgecheck(p, root, a, b, send_mode=1)
+    # separate tables, and a workspace that is reused without being cleared
+    q = lib.bcast_q(p)
+    recv = torch.full((n, max(q, 1)), 99, dtype=torch.int32, device=DEV)
+    send = torch.full((n, max(q, 1)), 99, dtype=torch.int32, device=DEV)
+    if q:
+        lib.bcast_schedules_ws(p, root, a, b, recv, send, q, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(recv.cpu().numpy(), want[:, :q]) and np.array_equal(send.cpu().numpy(), want[:, q:])
+
+
+def test_calls_with_workspace_on_the_streamed_instance():
+    p = workloads.STREAMED_P
+    gold = streamed_golden()
+    ws = torch.empty(lib.bcast_schedules_workspace(p), dtype=torch.uint8, device=DEV)
+    whole = 0
+    for i, (a, b) in enumerate(workloads.streamed_chunks()):
+        dg = torch.zeros(1, dtype=torch.int64, device=DEV)
+        fl = torch.ones(1, dtype=torch.int32, device=DEV)
+        lib.bcast_schedules_digest_ws(p, 0, a, b, dg, fl, ws)
+        torch.cuda.synchronize()
+        got = int(dg.item()) & oracle.U64_MAX
+        assert f"{got:016x}" == gold["chunks"][i]["digest"] and int(fl.item()) == 0, i
+        whole ^= got
+    assert f"{whole:016x}" == gold["digest"]
+    # whole chunks live, with the edge sums, a root inside the range, and a long table by slices
+    for root, a, n in [(0, 17 * 2**26, 2**26), (1_500_000_000, 1_500_000_000 - 30_000_000, 2**26 + 12345)]:
+        dg, xs = ws_digest_and_edges(p, root, a, a + n, ws)
+        assert dg == oracle.digest(p, root, a, a + n, send_mode=1)
+        assert xs == oracle.edgecheck(p, root, a, a + n, send_mode=1)
+    n = 2**24 + 77
+    for root, a in [(0, 0), (1_500_000_000, 1_500_000_000 - 5_000_000)]:
+        t = ws_table(p, root, a, a + n, ws)
+        step = 2**21
+        for lo in range(0, n, step):
+            hi = min(lo + step, n)
+            want = oracle.schedules(p, root=root, r_begin=a + lo, r_end=a + hi, send_mode=1)
+            assert np.array_equal(t[lo:hi].cpu().numpy(), want), (root, a + lo)
+        del t
+
+
+def test_calls_with_workspace_argument_errors():
+    p = 4000037
+    q = lib.bcast_q(p)
+    t = torch.zeros((16, 2 * q), dtype=torch.int32, device=DEV)
+    small = torch.zeros(lib.bcast_schedules_workspace(p) - 1, dtype=torch.uint8, device=DEV)
+    dg = torch.zeros(1, dtype=torch.int64, device=DEV)
+    fl = torch.zeros(1, dtype=torch.int32, device=DEV)
+    with pytest.raises(lib.BcastError) as e:
+        lib.bcast_schedules_ws(p, 0, 0, 16, t, t, 2 * q, small, send_offset=q)
+    assert e.value.code == lib.BCAST_ENOMEM
+    with pytest.raises(lib.BcastError) as e:
+        lib.bcast_schedules_digest_ws(p, 0, 0, 16, dg, fl, None)
+    assert e.value.code == lib.BCAST_EINVAL
+    ws = torch.zeros(lib.bcast_schedules_workspace(p), dtype=torch.uint8, device=DEV)
+    with pytest.raises(lib.BcastError) as e:
+        lib.bcast_schedules_ws(p, p, 0, 16, t, t, 2 * q, ws, send_offset=q)
+    assert e.value.code == lib.BCAST_EINVAL
+    assert lib.bcast_schedules_workspace(0) == 0
+    torch.cuda.synchronize()

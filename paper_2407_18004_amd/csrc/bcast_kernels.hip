@@ -99,6 +99,11 @@ struct SchedParams {
   int64_t ld;
   int layout;
   DeepTable table;                  // kernels with kMemo only
+  // Entries of the send part that k_schedules<true, .> leaves open for k_fill_open (row of the
+  // launch << 5 | round), or null: then the kernel fills them in itself, by search.
+  unsigned long long *open_list;
+  uint32_t *open_count;             // entries claimed so far (may run past open_cap)
+  uint32_t open_cap;
 };
 
 // The run of wavefront `wave` (the same in all lanes) of this workgroup: first tile and number
@@ -197,11 +202,34 @@ __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
   return slice_words(q) + 16u * q + kQueueWords + kRecordWords;
 }
 
+// Hands n entries (one per lane with `mine`, as row of the launch << 5 | round) to the list that
+// k_fill_open works off after this kernel, if there is a list and it has room for all of them.
+// Returns whether it did (the same in all lanes).
+__device__ __forceinline__ bool publish_open(const SchedParams &prm, uint32_t n, bool mine,
+                                             unsigned long long entry, uint32_t lane) {
+  if (prm.open_list == nullptr || n == 0u) return n == 0u && prm.open_list != nullptr;
+  uint32_t base = 0;
+  if (lane == 0) base = atomicAdd(prm.open_count, n);
+  base = lane0_of(base);
+  if (base >= prm.open_cap) return false;            // full
+  if (n > prm.open_cap - base) {                     // the claim does not fit: its slots stay unused
+    if (base + lane < prm.open_cap) prm.open_list[base + lane] = ~0ull;     // fewer than 64 of them
+    return false;
+  }
+  const uint64_t who = __ballot(mine);
+  if (mine) prm.open_list[base + (uint32_t)__popcll(who & ((1ull << lane) - 1ull))] = entry;
+  return true;
+}
+
 __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
                                                const uint32_t *queue, uint64_t run_row0,
                                                uint32_t lo, uint32_t hi, uint32_t lane) {
   // The rows were stored by this wavefront; they must have landed before single
   // entries of them are overwritten.
+  if (publish_open(prm, hi - lo, lo + lane < hi,
+                   lo + lane < hi ? ((run_row0 + (queue[lo + lane] >> 5)) << 5) | (queue[lo + lane] & 31u) : 0ull,
+                   lane))
+    return;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (lo + lane < hi) {
     const uint32_t item = queue[lo + lane];
@@ -362,19 +390,56 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   const uint32_t end2 = end1 + lds_dyn[2u * wave_words + count_at];
   const uint32_t end3 = end2 + lds_dyn[3u * wave_words + count_at];
   const uint32_t mine = wave * kWave + lane;         // all four queues together hold < 256
-  if (mine < end3) {
+  const bool have_one = mine < end3;
+  uint64_t row = 0;
+  uint32_t k = 0;
+  if (have_one) {
     const uint32_t u = (mine >= end0 ? 1u : 0u) + (mine >= end1 ? 1u : 0u) + (mine >= end2 ? 1u : 0u);
     const uint32_t start = u == 0u ? 0u : u == 1u ? end0 : u == 2u ? end1 : end2;
     const uint32_t entry = lds_dyn[u * wave_words + slice_w + 16u * q + (mine - start)];
     uint32_t u_lo, u_tiles;
     run_of_wave(prm.runs, u, u_lo, u_tiles);
-    const uint64_t row = (uint64_t)u_lo * kWave + (entry >> 5);
-    const uint32_t k = entry & 31u;
+    row = (uint64_t)u_lo * kWave + (entry >> 5);
+    k = entry & 31u;
+  }
+  const uint32_t first = wave * kWave;               // this wavefront's share of the pool
+  const uint32_t n_mine = end3 > first ? (end3 - first < (uint32_t)kWave ? end3 - first : (uint32_t)kWave) : 0u;
+  if (n_mine == 0u || publish_open(prm, n_mine, have_one, (row << 5) | k, lane)) return;
+  if (have_one) {
     const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + row));
     uint32_t fl = 0;
     prm.send[row * (uint64_t)prm.ld + k] = search_entry(in, to_processor(in, v, k), k, fl);
   }
 }
+
+// The entries k_schedules<true, .> left open, from the table itself: sendblock[k] of rank r is
+// recvblock[k] of its to-processor (Condition 2), whose row the same launch has written if it
+// is in the range of the call; if not, by a search as before.
+__global__ __launch_bounds__(kBlock) void k_fill_open(SchedParams prm) {
+  const Instance in = make_instance(prm.p, prm.q, prm.root);
+  // every claim that fit was written in full; the one claim that reached past the end of the
+  // list marked its slots unused; later claims start beyond the end
+  const uint32_t claimed = *prm.open_count;
+  const uint32_t n = claimed < prm.open_cap ? claimed : prm.open_cap;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+    const unsigned long long item = prm.open_list[i];
+    if (item == ~0ull) continue;                     // a slot no claim that fit covers
+    const uint64_t row = item >> 5;
+    const uint32_t k = (uint32_t)(item & 31u);
+    const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + row));
+    const uint32_t t = to_processor(in, v, k);       // virtual rank of the to-processor
+    const uint64_t t_phys = (uint64_t)t + prm.root >= prm.p ? (uint64_t)t + prm.root - prm.p : (uint64_t)t + prm.root;
+    int val;
+    if (t_phys >= prm.r_begin && t_phys - prm.r_begin < prm.n_ranks) {
+      val = prm.recv[(t_phys - prm.r_begin) * (uint64_t)prm.ld + k];
+    } else {
+      uint32_t fl = 0;
+      val = search_entry(in, t, k, fl);
+    }
+    prm.send[row * (uint64_t)prm.ld + k] = val;
+  }
+}
+
 
 // ------------------------------------------------------------------- digest
 
@@ -1149,12 +1214,6 @@ int bcast_skips(uint32_t p, uint32_t *skips, int *q_out) {
   return BCAST_OK;
 }
 
-// Bytes of the workspace of the *_ws calls: the table of deep entries.
-size_t bcast_schedules_workspace(uint32_t p) {
-  if (host_q(p) < 0) return 0;
-  return (size_t)kDeepMaxEntries * sizeof(uint4) + 256u;
-}
-
 }  // extern "C"
 
 namespace {
@@ -1162,6 +1221,13 @@ namespace {
 // The table of deep entries of p in the caller's workspace (built on the stream, before the
 // kernel that reads it), or none: no workspace, or p has too few levels above the deep ones.
 // Returns false when a launch failed.
+// Workspace of the *_ws calls: [table of deep entries][count of open entries][open entries].
+constexpr size_t kTableBytes = (size_t)kDeepMaxEntries * sizeof(uint4) + 256u;
+uint32_t open_list_capacity(uint32_t p) {
+  const uint64_t want = (uint64_t)p / 8u + 4096u;    // p = 1,000,003 leaves 39,000 open, p = 2^20 + 1 fewer than p / 16
+  return (uint32_t)(want < (1ull << 22) ? want : (1ull << 22));
+}
+
 // Building the table takes one small kernel ahead of the main one, some 15 us from launch to end;
 // it pays from a few million ranks on (measured on MI355X: tables of 2^23 ranks 1.4 times
 // faster, p = 1,000,003 10 % slower), so shorter ranges are computed without it.
@@ -1220,9 +1286,25 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
   const bool memo = prm.table.entries != nullptr;
   const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
                            : (size_t)lone_block_words(prm.q) * 4u;
+  prm.open_list = nullptr; prm.open_count = nullptr; prm.open_cap = 0;
+  if (share && workspace) {                          // entries left open go to a list, see k_fill_open
+    const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256) + kTableBytes;
+    prm.open_count = reinterpret_cast<uint32_t *>(base);
+    prm.open_list = reinterpret_cast<unsigned long long *>(base + 256u);
+    prm.open_cap = open_list_capacity(p);
+    hipLaunchKernelGGL(k_u32_zero, dim3(1), dim3(64), 0, (hipStream_t)stream, prm.open_count);
+    if (!launch_ok()) return BCAST_EHIP;
+  }
   if (share) {
     if (memo) hipLaunchKernelGGL((k_schedules<true, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
     else hipLaunchKernelGGL((k_schedules<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
+    if (prm.open_list) {
+      if (!launch_ok()) return BCAST_EHIP;
+      const uint64_t most = n * 4u < prm.open_cap ? n * 4u : prm.open_cap;      // at most four per rank
+      const uint64_t blocks_fill = (most + kBlock - 1) / kBlock;
+      hipLaunchKernelGGL(k_fill_open, dim3((unsigned)(blocks_fill < 2048u ? (blocks_fill ? blocks_fill : 1u) : 2048u)),
+                         dim3(kBlock), 0, (hipStream_t)stream, prm);
+    }
   } else {
     if (memo) hipLaunchKernelGGL((k_schedules<false, true>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
     else hipLaunchKernelGGL((k_schedules<false, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
@@ -1275,7 +1357,7 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
 
 // workspace argument of a *_ws call: NULL is an error there, and so is one that is too small
 int check_workspace(uint32_t p, const void *workspace, size_t workspace_bytes) {
-  const size_t need = bcast_schedules_workspace(p);
+  const size_t need = host_q(p) < 0 ? 0 : kTableBytes + 256u + (size_t)open_list_capacity(p) * 8u + 256u;
   if (need == 0 || !workspace) return BCAST_EINVAL;
   return workspace_bytes < need ? BCAST_ENOMEM : BCAST_OK;
 }
@@ -1283,6 +1365,13 @@ int check_workspace(uint32_t p, const void *workspace, size_t workspace_bytes) {
 }  // namespace
 
 extern "C" {
+
+// Bytes of the workspace of the *_ws calls: the table of deep entries and the list of entries
+// left open.
+size_t bcast_schedules_workspace(uint32_t p) {
+  if (host_q(p) < 0) return 0;
+  return kTableBytes + 256u + (size_t)open_list_capacity(p) * 8u + 256u;
+}
 
 int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
                     int32_t *recv, int32_t *send, int64_t ld, void *stream) {

@@ -89,6 +89,39 @@ def batched_instances(n_inst: int = 65536, m: int = 4096, seed: int = 42,
     return p.astype(np.uint32), root.astype(np.uint32), ranks
 
 
+def batched_ranks_on_device(p: np.ndarray, m: int, seed: int, first: int, device):
+    """The ranks of batched_instances(len(p), m, seed, first), generated on `device` with torch
+    (int32 tensor [len(p)][m] holding the uint32 values): the same counter-based draws in
+    64-bit wrap-around arithmetic, for workloads too large to draw on the host in reasonable time."""
+    import torch
+
+    def u64(x):                                    # a Python int as the int64 with the same bits
+        x &= (1 << 64) - 1
+        return x - (1 << 64) if x >= (1 << 63) else x
+
+    def shr(z, k):                                 # logical shift right of int64 bit patterns
+        return (z >> k) & ((1 << (64 - k)) - 1)
+
+    def mix(z):
+        z = z + u64(0x9E3779B97F4A7C15)
+        z = (z ^ shr(z, 30)) * u64(0xBF58476D1CE4E5B9)
+        z = (z ^ shr(z, 27)) * u64(0x94D049BB133111EB)
+        return z ^ shr(z, 31)
+
+    n_inst = len(p)
+    inst = torch.arange(first, first + n_inst, dtype=torch.int64, device=device)
+    stream = (inst << 8) + 13
+    seed_mixed = u64(int(_mix(np.asarray(seed, dtype=np.uint64))))
+    key = mix(stream ^ seed_mixed)[:, None]
+    j = torch.arange(m, dtype=torch.int64, device=device)[None, :]
+    z = mix(key + j)                               # uint64 draws as int64 bit patterns
+    pt = torch.from_numpy(np.asarray(p, dtype=np.int64)).to(device)[:, None]
+    hi, lo = shr(z, 32), z & 0xFFFFFFFF            # z mod p from its halves: p < 2^31, no overflow
+    two32 = (1 << 32) % pt
+    r = ((hi % pt) * two32 + lo % pt) % pt
+    return r.to(torch.int32)
+
+
 def q_of(p) -> np.ndarray:
     """ceil(log2 p) for arrays of processor counts (layout only, no schedule math)."""
     p = np.asarray(p, dtype=np.int64)

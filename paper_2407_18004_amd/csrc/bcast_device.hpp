@@ -565,9 +565,16 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
 // state in which the search goes on (remaining deep levels, D, M; the cursor is past the end of
 // the list and no deep call is pending).  16 bytes per rho:
 //   x: bits 0-10 remaining deep levels (bit i: level first_deep + i), 11-14 baseblock's level
-//      - first_deep, 15-18 K, bit 31 valid
+//      - first_deep, 15-18 K, 19-29 the deep levels Algorithm 3 takes (same numbering), bit 31 valid
 //   y: D | M << 16
-//   z, w: accepted levels - first_deep, four bits each, round k at nibble k (z: rounds 0-7)
+//   z, w: accepted levels - first_deep, four bits each, round k at nibble k (z: rounds 0-7);
+//      w bits 16-26: the violations of Algorithm 6 in the deep rounds (as top_down_level collects
+//      them: the round of level j at bit q - 1 - j) for a rank that arrives with e = S
+// Algorithm 6 sees more of a rank than rho in these rounds: its e.  After the levels above, e is
+// S less the number of odd skips met on the way: S itself for half of all ranks (for all of them
+// when every skip is a power of two); those take the violations from the entry and the blocks to
+// send from the levels taken (c is minus the last level taken, or what it was above), the others
+// walk through the rounds.
 // rho < 2 (the baseblock's level lies above, or the descent has ended there) has no entry: such
 // ranks take the levels one by one.
 struct DeepTable {
@@ -594,10 +601,14 @@ __device__ __forceinline__ uint4 deep_entry_build(uint32_t pm1, uint32_t q, uint
   TopDown s;
   s.rem = rho; s.jb = 0; s.closed = false;
   s.W = (int)rho - 2;
-  s.pathr = 0; s.anom = 0; s.e = 0; s.c = 0; s.viol = 0;
-  uint32_t unused = 0;
-  for (uint32_t j = first_deep; j <= q; ++j)
-    top_down_level<false, false>(pm1, q, j, s, unused, [](uint32_t, int) {});
+  s.pathr = 0; s.anom = 0; s.c = 0; s.viol = 0;
+  s.e = deep_table_rhos(pm1, first_deep);              // S: Algorithm 6's e of half of all ranks
+  uint32_t unused = 0, taken = 0;
+  for (uint32_t j = first_deep; j <= q; ++j) {
+    const uint32_t before = s.rem;
+    top_down_level<true, false>(pm1, q, j, s, unused, [](uint32_t, int) {});
+    taken |= (uint32_t)(s.rem != before) << (j - first_deep);
+  }
   uint32_t lv_lo = 0, lv_hi = 0, n_out = 0;
   bool all_deep = true;
   auto note = [&](uint32_t k, int val) {
@@ -616,12 +627,12 @@ __device__ __forceinline__ uint4 deep_entry_build(uint32_t pm1, uint32_t q, uint
   const uint32_t live_deep = a.live >> first_deep;
   const bool ok = !anomaly && all_deep && s.rem == 0u && s.jb >= first_deep && s.jb - first_deep < 16u &&
                   a.pathr == 0u && (int)a.j < 0 && a.k == n_out && a.k <= 11u && a.k < q &&
-                  live_deep < 2048u && a.D < 65536u && a.M < 65536u &&
+                  live_deep < 2048u && a.D < 65536u && a.M < 65536u && taken < 2048u && s.viol < 2048u &&
                   (a.live & ((1u << first_deep) - 1u)) == ((1u << first_deep) - 1u);
   if (!ok) return e;
-  e.x = live_deep | ((s.jb - first_deep) << 11) | (a.k << 15) | 0x80000000u;
+  e.x = live_deep | ((s.jb - first_deep) << 11) | (a.k << 15) | (taken << 19) | 0x80000000u;
   e.y = a.D | (a.M << 16);
-  e.z = lv_lo; e.w = lv_hi;
+  e.z = lv_lo; e.w = lv_hi | (s.viol << 16);
   return e;
 }
 
@@ -730,10 +741,21 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
     generic = generic && (e.x >> 31) != 0u;
     AscentState a;
     if (generic) {
-      // Algorithm 6 goes through the deep levels as ever (its e and c are the rank's own); the
-      // descent and Algorithm 3's baseblock come from the entry
-      for (; j <= q; ++j) top_down_level<true, false, false>(in.pm1, q, j, s, unused, put_send);
+      // the descent and Algorithm 3's baseblock come from the entry, and so do the deep rounds
+      // of Algorithm 6 if the rank arrives with e = S; otherwise Algorithm 6 walks through them
       const uint32_t fd = table.first_deep;
+      if (s.e == table.n_rho) {
+        const uint32_t taken = (e.x >> 19) & 0x7FFu;
+        for (; j < q; ++j) {
+          const uint32_t upto = taken & ((2u << (j - fd)) - 1u);         // levels taken so far
+          const int last = (int)(fd + 31u) - (int)__clz((int)upto);      // the last of them
+          s.c = upto != 0u ? -last : s.c;
+          send_row[q - j] = (int8_t)s.c;
+        }
+        s.viol = (s.viol << (q - fd)) | ((e.w >> 16) & 0x7FFu);
+      } else {
+        for (; j <= q; ++j) top_down_level<true, false, false>(in.pm1, q, j, s, unused, put_send);
+      }
       s.jb = fd + ((e.x >> 11) & 15u);
       const uint32_t n_acc = (e.x >> 15) & 15u;
       for (uint32_t k = 0; k < n_acc; ++k) {
@@ -899,18 +921,21 @@ __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint
   const uint32_t q = in.q;
   const uint32_t two_q = 2u * q;
   const bool is_root = v == 0;
-  uint64_t seen = 0;
+  // `have`: what the rank may send so far, b - q from the start (not for the root, which is not
+  // held to Condition 4), then every block it has received.  q receive entries fill it up to
+  // exactly {-q..-1} + {b} if and only if they are the set of Condition 3 (one entry too few of
+  // that set leaves a gap, since b - q itself is not among them).
+  uint64_t have = is_root ? 0ull : 1ull << b;
   uint32_t u_max = 0, bad_c4 = 0;
-  const uint64_t always = is_root ? ~0ull : 1ull << b;         // b - q may always be sent
   for (uint32_t k = 0; k < q; ++k) {
     const uint32_t ur = (uint32_t)((int)row[k] + (int)q);        // value + q: in range iff < 2q
     const uint32_t us = (uint32_t)((int)row[q + k] + (int)q);
     u_max = ur > u_max ? ur : u_max;
     u_max = us > u_max ? us : u_max;
-    const uint64_t allowed = seen | always;
-    bad_c4 |= (uint32_t)(((allowed >> (us & 63u)) & 1ull) == 0ull && k != 0);  // round 0: send0
-    seen |= 1ull << (ur & 63u);
+    bad_c4 |= (uint32_t)(((have >> (us & 63u)) & 1ull) == 0ull && k != 0);  // round 0: send0
+    have |= 1ull << (ur & 63u);
   }
+  bad_c4 = is_root ? 0u : bad_c4;
   // sendblock[0] is b - q by Condition 4 (value + q = b); the root sends block k in round k
   bool bad_s0 = !is_root && q > 0 && (uint32_t)((int)row[q] + (int)q) != (uint32_t)b;
   if (__any(is_root)) {
@@ -919,8 +944,8 @@ __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint
   }
   const bool bad_range = u_max >= two_q && q > 0;
   const uint64_t low = q >= 32 ? 0xFFFFFFFFull : ((1ull << q) - 1ull);
-  const uint64_t want = is_root ? low : ((low ^ (1ull << b)) | (1ull << (q + (uint32_t)b)));
-  flags = (seen == want && !bad_range ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
+  const uint64_t want = is_root ? low : (low | (1ull << (q + (uint32_t)b)));
+  flags = (have == want && !bad_range ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
           (bad_c4 ? BCAST_F_COND4 : 0u) | (bad_range ? BCAST_F_RANGE : 0u);
 
   // ten six-bit fields per word; full words first, then the tail

@@ -641,7 +641,8 @@ def test_doubling_chain_from_the_gpu_table_and_errors():
 def test_schedules_by_doubling_equal_the_oracle():
     # table(p) for p = m 2^j as table(m) doubled j times, against the oracle's table(p):
     # powers of two (m = 1), twice an odd number, 3 * 2^20, workload 2's neighbour, odd p
-    for p in [1, 2, 4, 6, 12, 18, 64, 1000, 1001, 4096, 65536, 999_998, 1_000_004, 3 * 2**20, 2**22]:
+    for p in [1, 2, 4, 6, 12, 18, 64, 1000, 1001, 4096, 65536, 131072, 262146, 999_998, 1_000_004, 3 * 2**20, 5 * 2**18, 2**22,
+              2**24]:
         q = lib.bcast_q(p)
         ws = torch.full((lib.bcast_schedules_doubling_workspace(p),), 0x5A, dtype=torch.uint8, device=DEV)
         out = torch.full((p, 2 * q), 77, dtype=torch.int32, device=DEV)

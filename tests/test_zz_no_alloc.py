@@ -29,9 +29,11 @@ def with_workspace(p, n, roots, sched=None):
 def without_allocation(p, n, roots, sched, vd):
     """vd: a verdict buffer allocated beforehand; nothing is allocated around the call."""
     vd.fill_(0xCD)
-    before = torch.cuda.memory_allocated()
+    # the number of allocations torch's allocator has served so far (frees by the garbage
+    # collector of tensors of earlier tests do not touch it)
+    before = torch.cuda.memory_stats()["allocation.all.allocated"]
     lib.bcast_simulate_noalloc(p, n, roots, sched, vd)
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
     torch.cuda.synchronize()
     return verdicts_from_bytes(vd[: len(roots) * VERDICT_BYTES].cpu().numpy().tobytes())
 

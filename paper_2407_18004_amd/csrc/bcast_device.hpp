@@ -157,13 +157,30 @@ __device__ __forceinline__ uint32_t virtual_rank(const Instance &in, uint32_t r)
 struct TrackOff { static constexpr bool value = false; };
 struct TrackOn { static constexpr bool value = true; };
 
-// How far the difference x - y of a test "x >= y" is from flipping: the test
-// keeps its outcome as long as the difference moves by no more than this.
-__device__ __forceinline__ uint32_t flip_distance(uint32_t x, uint32_t y) {
-  // operands are below 2^32 and differ by less than 2^32; a difference of 2^31 or more comes
-  // out as a distance of at least 2^29, still far more than any step a record is used across
-  const int dxy = (int)(x - y);
-  return (uint32_t)(dxy ^ (dxy >> 31));           // d for d >= 0, -1 - d for d < 0
+// How far the difference x - y of a test "x >= y" is from flipping: the test keeps its outcome as
+// long as the difference moves by no more than x - y (x >= y) or y - x - 1 (x < y).
+// The records keep |x - y|, which is one instruction: exact for x >= y and one too many for
+// x < y; every use of a margin made of these asks for one more than the shift (the "+ 1" in
+// stretch_shift and in the test on the top levels), which covers it.
+__device__ __forceinline__ uint32_t abs_difference(uint32_t x, uint32_t y) {
+#ifdef BCAST_DEVICE_CODE_ON_HOST
+  return x > y ? x - y : y - x;
+#else
+  uint32_t d;
+  asm("v_sad_u32 %0, %1, %2, 0" : "=v"(d) : "v"(x), "v"(y));
+  return d;
+#endif
+}
+
+// How far the difference of any test of the lockstep stretch can move when D moves by dD and M by
+// dM (as unsigned differences): its two sides are D + c, M + c or constants, so it moves by dD,
+// dM, their difference, or not at all.  (M turns into a D + c or a constant along the way, which
+// only makes it move less.)  Plus the one that the margins ask for.
+__device__ __forceinline__ uint32_t stretch_shift(uint32_t dD, uint32_t dM) {
+  auto mag = [](uint32_t d) { const int s = (int)d; return (uint32_t)(s < 0 ? -s : s); };
+  const uint32_t a = mag(dD), b = mag(dM), c = mag(dD - dM);
+  const uint32_t ab = a > b ? a : b;
+  return (ab > c ? ab : c) + 1u;
 }
 
 // One pass over the levels j = 1 .. q, i.e. over skip[q-1] down to skip[0],
@@ -216,7 +233,7 @@ template <bool kSend, bool kTrack, bool kDescent = true, typename EmitSend>
 __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_t j, TopDown &s,
                                                uint32_t &margin, EmitSend emit_send) {
   auto see = [&](uint32_t x, uint32_t y) {
-    if (kTrack) { const uint32_t fd = flip_distance(x, y); margin = fd < margin ? fd : margin; }
+    if (kTrack) { const uint32_t fd = abs_difference(x, y); margin = fd < margin ? fd : margin; }
   };
   const uint32_t sk = skip_at_level(pm1, j);            // the same in all lanes: a scalar
   see(s.rem, sk);
@@ -247,9 +264,11 @@ __device__ __forceinline__ void top_down_level(uint32_t pm1, uint32_t q, uint32_
   if (!kDescent) return;
   const int ski = (int)sk;
   const int t = s.W - ski;
-  see((uint32_t)(t + 1), 0u);
-  see((uint32_t)t, 0u);
-  see((uint32_t)(t + 1), sk);
+  // the tests on t below (t >= -1, t >= 0, skip <= t + 1) between non-negative numbers: W >= -1
+  const uint32_t w1 = (uint32_t)(s.W + 1);
+  see(w1, sk);
+  see(w1, sk + 1u);
+  see(w1, 2u * sk);
   const bool take = !closes && t >= -1;                 // push (t >= 0) or accept (t = -1)
   // The call made for this index would look at the index again (skip + 1 <=
   // D - skip) and that look must fail.  It does whenever the level above was
@@ -415,7 +434,11 @@ __device__ __forceinline__ uint32_t deep_level_mask(uint32_t pm1) {
 // The ascent from state `a` on.  kPrefix: only the first stretch (while levels with small skips
 // remain), with `a` holding the state it ends in; a search that stops there because it runs out of
 // pending calls is complete as far as it goes and raises nothing.
-template <bool kPrefix, typename Emit>
+// kFlat: every move runs through one body without branches.  That costs more instructions per
+// move than the one branch a wavefront in lockstep takes, and fewer than all the branches a
+// wavefront of unrelated ranks takes one after the other: for lists of arbitrary ranks and for
+// the searches that answer violations.
+template <bool kPrefix, bool kFlat = false, typename Emit>
 __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_t jb, uint32_t k_last,
                                                AscentState &a, uint32_t anom_in, bool &anomaly,
                                                Emit emit, LockstepCache &cache, bool use_cache) {
@@ -439,7 +462,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
   auto move = [&](auto track_tag) {
     constexpr bool kTrack = decltype(track_tag)::value;
     auto see = [&](uint32_t x, uint32_t y) {
-      if (kTrack) { const uint32_t fd = flip_distance(x, y); margin = fd < margin ? fd : margin; }
+      if (kTrack) { const uint32_t fd = abs_difference(x, y); margin = fd < margin ? fd : margin; }
     };
     uint32_t jj, a, t;
     bool post;
@@ -487,6 +510,34 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
     j = ret ? kEndLevel : next_level(live, jj);
     go = k < k_stop && !((int)j < 0 && pathr == 0);
   };
+  auto move_flat = [&]() {
+    const bool pop = (int)j < 0;                          // list exhausted: back to the pending call
+    const uint32_t jj = pop ? 31u - (uint32_t)(__ffs((int)pathr) - 1) : j;
+    const uint32_t a = skip_at_level(pm1, jj);
+    const uint32_t t = pop ? D : D - a;
+    const bool pass = !pop && a <= D && t >= M;
+    const bool rec = pass && t >= sk1;                    // recursive call on r' + skip[e]
+    anom |= (uint32_t)(rec && a <= t && t - a >= M);
+    const bool post = pop || (pass && !rec);
+    const uint32_t bit = 0x80000000u >> jj;
+    D = pop ? D + a : (rec ? t : D);
+    pathr ^= (pop || rec) ? bit : 0u;                     // a return clears the bit, a call sets it
+    const bool accept = post && D >= sk1;
+    if (accept) emit(k, jj == 0 ? b : -(int)jj);
+    live ^= accept ? 1u << jj : 0u;
+    M = accept ? (sk1 > t + 1u ? sk1 : t + 1u) : M;
+    k += (uint32_t)accept;
+    sk1 = accept ? skip_at_level(pm1, (q - k - 1u) & 31u) : sk1;
+    j = (post && !accept) ? kEndLevel : next_level(live, jj);
+    go = k < k_stop && !((int)j < 0 && pathr == 0);
+  };
+  static_assert(!(kFlat && kPrefix), "the first stretch alone is not run flat");
+  if (kFlat) {
+    for (; it < cap && go; ++it) move_flat();
+    if (kPrefix) { a.D = D; a.M = M; a.sk1 = sk1; a.k = k; a.j = j; a.live = live; a.pathr = pathr; }
+    anomaly = anomaly || anom != 0 || (!kPrefix && k < k_stop) || it >= cap;
+    return k;
+  }
   for (; it < cap && go && (live & deep) != 0u; ++it) move(TrackOff{});
   if (kPrefix) {
     a.D = D; a.M = M; a.sk1 = sk1; a.k = k; a.j = j; a.live = live; a.pathr = pathr;
@@ -503,7 +554,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
       if (cache.mem[kRecValid] && k0 == cache.mem[kRecK] && l0 == cache.mem[kRecLive] && p0 == cache.mem[kRecPathr] &&
           j0 == cache.mem[kRecJ]) {
         const uint32_t dD = D - cache.D, dM = M - cache.M;
-        const uint32_t far = flip_distance(D, cache.D) + flip_distance(M, cache.M) + 2u;
+        const uint32_t far = stretch_shift(dD, dM);
         const uint32_t dD0 = lane0_of(dD), dM0 = lane0_of(dM);   // read by all lanes, whatever the tests say
         const bool ok = dD == dD0 && dM == dM0 && far <= cache.mem[kRecMargin] &&
                         it + cache.mem[kRecIters] <= cap;
@@ -525,7 +576,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
   if (record) {
     for (; it < cap && go; ++it) move(TrackOn{});
     // usable if it ran to the end without incident and no lane can have left the others
-    const uint32_t apart = flip_distance(D_in, lane0_of(D_in)) + flip_distance(M_in, lane0_of(M_in)) + 2u;
+    const uint32_t apart = stretch_shift(D_in - lane0_of(D_in), M_in - lane0_of(M_in));
     const uint32_t m_all = wave_min32(margin);
     const uint32_t apart_all = wave_max32(apart);
     const bool fine = k == q && anom == 0;
@@ -541,7 +592,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
   return k;
 }
 
-template <typename Emit>
+template <bool kFlat = false, typename Emit>
 __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32_t q,
                                                 uint32_t jb, uint32_t k_last, int W,
                                                 uint32_t pathr, uint32_t anom_in,
@@ -549,7 +600,7 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
                                                 LockstepCache &cache, bool use_cache) {
   (void)p;
   AscentState a = ascent_start(pm1, q, jb, W, pathr, emit);
-  return ascent_run<false>(pm1, q, jb, k_last, a, anom_in, anomaly, emit, cache, use_cache);
+  return ascent_run<false, kFlat>(pm1, q, jb, k_last, a, anom_in, anomaly, emit, cache, use_cache);
 }
 
 // Table of deep entries.
@@ -651,7 +702,7 @@ struct MemoOut {
   uint32_t rho, room;
 };
 
-template <bool kMemo>
+template <bool kMemo, bool kFlat = false>
 __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
                                                         int8_t *recv_row, int8_t *send_row,
                                                         int &b_out, uint32_t &flags,
@@ -681,7 +732,7 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   if (n_top >= 4u) {
     const uint32_t dv = v - cache.top_v;
     const uint32_t dv0 = lane0_of(dv);
-    const uint32_t away = flip_distance(v, cache.top_v);
+    const uint32_t away = abs_difference(v, cache.top_v);
     const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == dv0 &&
                       away + 1u <= cache.mem[kTopMargin];
     if (!__any(!near)) {
@@ -788,8 +839,8 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
     send_row[0] = (int8_t)(b - (int)q);
   }
   if (!kMemo)
-    produced = recv_ascent(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
-                           cache, use);
+    produced = recv_ascent<kFlat>(in.p, in.pm1, q, jb, q - 1u, s.W, s.pathr, s.anom, anomaly, put_recv,
+                                  cache, use);
   if (produced != q || anomaly) flags |= BCAST_F_SEARCH;
   if (__popc(viol) > 4) flags |= BCAST_F_VIOLATIONS;
   return viol;
@@ -861,6 +912,7 @@ __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint3
 
 // recvblock[k] of virtual rank t alone, by a receive search that stops once
 // entry k is out: what a violation of Algorithm 6 in round k asks for.
+template <bool kFlat = false>
 __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint32_t k,
                                             uint32_t &flags) {
   const uint32_t q = in.q;
@@ -875,7 +927,7 @@ __device__ __forceinline__ int search_entry(const Instance &in, uint32_t t, uint
   uint32_t got;
   LockstepCache none;
   lockstep_cache_init(none, nullptr);
-  got = recv_ascent(in.p, in.pm1, q, jbt, k, s.W, s.pathr, s.anom, anomaly_t, take, none, false);
+  got = recv_ascent<kFlat>(in.p, in.pm1, q, jbt, k, s.W, s.pathr, s.anom, anomaly_t, take, none, false);
   if (got <= k || anomaly_t) flags |= BCAST_F_SEARCH;
   return val;
 }
@@ -887,13 +939,14 @@ __device__ __forceinline__ uint32_t to_processor(const Instance &in, uint32_t v,
 }
 
 // Phase three: the remaining violations of Algorithm 6, each by its own search.
+template <bool kFlat = false>
 __device__ __forceinline__ uint32_t resolve_by_search(const Instance &in, uint32_t v,
                                                       uint32_t viol, int8_t *send_row) {
   uint32_t flags = 0;
   while (viol != 0) {
     const uint32_t k = (uint32_t)(__ffs((int)viol) - 1);
     viol &= viol - 1u;
-    send_row[k] = (int8_t)search_entry(in, to_processor(in, v, k), k, flags);
+    send_row[k] = (int8_t)search_entry<kFlat>(in, to_processor(in, v, k), k, flags);
   }
   return flags;
 }

@@ -774,7 +774,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         lockstep_cache_init(none, nullptr);
         const uint32_t v = virtual_rank(in, r);
         open_v[wave][lane] = v;
-        viol = compute_rank_phase1(in, v, recv_row, send_row, b, flags, none, false);
+        DeepTable no_table;
+        no_table.entries = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
+        MemoOut unused;
+        viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none, false,
+                                                no_table, unused);
       } else {                           // rank outside the instance: marked row
         for (uint32_t k = 0; k < 2u * q; ++k) recv_row[k] = (int8_t)kInvalidByte;
         if (prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
@@ -798,7 +802,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         const uint32_t item = open_entry[wave][e];
         const uint32_t owner = item >> 5, k = item & 31u;
         uint32_t fl = 0;
-        const int val = search_entry(in, to_processor(in, open_v[wave][owner], k), k, fl);
+        const int val = search_entry<true>(in, to_processor(in, open_v[wave][owner], k), k, fl);
         reinterpret_cast<int8_t *>(lds[wave])[owner * 2u * q + q + k] = (int8_t)val;
       }
       wave_lds_sync();

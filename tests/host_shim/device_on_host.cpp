@@ -123,7 +123,9 @@ uint64_t shim_last_top_replays(void) { return g_top_replays; }
 
 // rows: m rows of 2q int32 (recv then send) for the physical ranks given.
 // flags_out/hash_out (may be NULL): per-rank flags and row hash.
-int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint64_t m,
+// flat != 0: with the search run through its one branch-free body, as the kernel for lists of
+// arbitrary ranks runs it.
+int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint64_t m, int flat,
                          int32_t *rows, uint32_t *flags_out, uint64_t *hash_out) {
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
@@ -132,7 +134,19 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
     memset(buf, 0x55, sizeof buf);
     int b = 0;
     const uint32_t v = virtual_rank(in, ranks[i]);
-    uint32_t fl = compute_rank(in, v, buf, buf + q, b);
+    uint32_t fl;
+    if (flat) {
+      LockstepCache none;
+      lockstep_cache_init(none, nullptr);
+      DeepTable no_table;
+      no_table.entries = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
+      MemoOut unused;
+      const uint32_t viol = compute_rank_phase1<false, true>(in, v, buf, buf + q, b, fl, none, false,
+                                                             no_table, unused);
+      fl |= resolve_by_search<true>(in, v, viol, buf + q);
+    } else {
+      fl = compute_rank(in, v, buf, buf + q, b);
+    }
     for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = buf[k];
     uint64_t h = 0;
     uint32_t fl2 = 0;

@@ -10,6 +10,7 @@
 #pragma once
 #include <stdint.h>
 
+#define BCAST_DEVICE_CODE_ON_HOST 1   // the one instruction written in assembly has a C form for this
 #define __device__
 #define __forceinline__ inline
 #define __host__

@@ -26,7 +26,7 @@ def shim():
                         "-Wall", "-o", SHIM_SO, src], check=True)
     lib = ctypes.CDLL(SHIM_SO)
     lib.shim_schedules_ranks.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
-                                         ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p]
     lib.shim_digest_row.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
@@ -50,13 +50,13 @@ def shim():
     return lib
 
 
-def shim_rows(lib, p, root, ranks):
+def shim_rows(lib, p, root, ranks, flat=False):
     ranks = np.ascontiguousarray(ranks, dtype=np.uint32)
     q = oracle.q_of(p)
     rows = np.zeros((ranks.size, 2 * q), dtype=np.int32)
     flags = np.zeros(ranks.size, dtype=np.uint32)
     hashes = np.zeros(ranks.size, dtype=np.uint64)
-    got_q = lib.shim_schedules_ranks(p, root, ranks.ctypes.data, ranks.size,
+    got_q = lib.shim_schedules_ranks(p, root, ranks.ctypes.data, ranks.size, int(flat),
                                      rows.ctypes.data if rows.size else None,
                                      flags.ctypes.data, hashes.ctypes.data)
     assert got_q == q
@@ -102,6 +102,8 @@ def test_all_ranks_small_p(shim):
         want = oracle.schedules(p, send_mode=1)
         assert np.array_equal(rows, want), p
         assert not flags.any(), p
+        flat_rows, flat_flags, _ = shim_rows(shim, p, 0, np.arange(p), flat=True)    # the branch-free search
+        assert np.array_equal(flat_rows, want) and not flat_flags.any(), p
         dg, fl = oracle.digest(p, 0, 0, p)
         assert int(np.bitwise_xor.reduce(hashes)) == dg and fl == 0
 
@@ -117,6 +119,8 @@ def test_roots_and_large_p(shim):
         want = oracle.schedules_ranks(p, root, ranks, send_mode=1)
         assert np.array_equal(rows, want), p
         assert not flags.any()
+        flat_rows, flat_flags, _ = shim_rows(shim, p, root, ranks, flat=True)
+        assert np.array_equal(flat_rows, want) and not flat_flags.any(), p
         for j in range(0, len(ranks), 97):
             h, fl = oracle.digest_row(p, root, int(ranks[j]), want[j, :want.shape[1] // 2],
                                       want[j, want.shape[1] // 2:])

@@ -21,17 +21,17 @@ int orc_q(int64_t p)
     return q;
 }
 
-/* Algorithm 2.  The division is integer division, so the new skip is the old
- * one halved and rounded up. */
+/* Algorithm 2: from skip[q] = p downwards, every skip is the one above it
+ * halved with rounding up (what is left after taking away the rounded-down
+ * half). */
 int orc_skips(int64_t p, int64_t *skip)
 {
     int q = orc_q(p);
     if (q < 0) return -1;
-    int k = q;
-    skip[k] = p;
-    while (k > 0) {
-        skip[k - 1] = skip[k] - skip[k] / 2;
-        k = k - 1;
+    skip[q] = p;
+    for (int k = q; k > 0; k--) {
+        int64_t lower_half = skip[k] / 2;
+        skip[k - 1] = skip[k] - lower_half;
     }
     return q;
 }
@@ -42,15 +42,13 @@ int orc_skips(int64_t p, int64_t *skip)
  * no skip to look at; the only rank is the root and its baseblock is q. */
 static int baseblock_sk(const int64_t *skip, int q, int64_t r)
 {
-    if (q == 0) return q;
-    int k = q;
-    int64_t rp = 0;
-    do {
-        k = k - 1;
-        if (rp + skip[k] == r) return k;
-        else if (rp + skip[k] < r) rp = rp + skip[k];
-    } while (k != 0);
-    return q;
+    int64_t rp = 0;                       /* r': the skips taken so far */
+    for (int k = q - 1; k >= 0; k--) {
+        int64_t with_k = rp + skip[k];
+        if (with_k == r) return k;        /* the sum closes on r: k is its smallest index */
+        if (with_k < r) rp = with_k;      /* still short of r: the skip is part of the sequence */
+    }
+    return q;                             /* nothing closed: r = 0 */
 }
 
 int orc_baseblock(int64_t p, int64_t r)
@@ -90,41 +88,46 @@ static void unlink_index(recv_ctx *c, int e)
     PREV(c, NEXT(c, e)) = PREV(c, e);
 }
 
-/* Algorithm 4.  R, rp (r'), s, e are by value; k is handed back as the
- * result; idx[] and the list are shared.
+/* Algorithm 4: the depth-first search for processor R = p + r.  A call stands
+ * at intermediate processor rp (r') and goes down the list of remaining skip
+ * indices from e on.  R, rp, s and e belong to the call; the round k it has
+ * got to is handed back as its result; idx[] and the list are common to all
+ * calls.
  *
- * Reading of the one place the listing leaves open: after q indices have been
- * accepted there is no skip[k+1] to compare with.  The list is then empty, so
- * the loop ends anyway; the test after the recursive call is guarded by
- * "k = q: return" and counted as an anomaly if the frame's index is still
- * linked (it never is). */
+ * The one place the algorithm leaves open: once q indices are accepted there
+ * is no skip[k+1] to compare with.  The list is empty by then and the loop
+ * ends anyway; the test after a call that comes back with k = q is therefore
+ * "return", and it counts as an anomaly if the call's own index were still in
+ * the list (it never is). */
 static int allblocks(recv_ctx *c, int64_t rp, int64_t s, int e, int k, int depth)
 {
     const int64_t *skip = c->skip;
     const int64_t R = c->R;
     const int q = c->q;
     if (depth > c->st.max_depth) c->st.max_depth = depth;
-    while (e != -1) {
+    for (; e != -1; e = NEXT(c, e)) {
         c->st.scans++;
-        if (k < q && rp + skip[e] <= R - skip[k] && rp + skip[e] < s) {
-            if (rp + skip[e] <= R - skip[k + 1]) {
-                if (c->onpath[e + 1]) c->st.anomalies++;
-                c->onpath[e + 1]++;
-                c->st.calls++;
-                k = allblocks(c, rp + skip[e], s, e, k, depth + 1);
-                c->onpath[e + 1]--;
-            }
-            if (k >= q) {                       /* guard, see above */
-                if (c->linked[e + 1]) c->st.anomalies++;
-                return k;
-            }
-            if (rp > R - skip[k + 1]) return k;
-            s = rp + skip[e];                   /* canonical skip sequence found */
-            c->idx[k] = e;                      /* accept e, next k */
-            k = k + 1;
-            unlink_index(c, e);
+        if (k >= q) continue;                    /* nothing left to find; the list is empty */
+        const int64_t via_e = rp + skip[e];      /* the processor one skip[e] further on */
+        /* of use for round k: no later than the from-processor of that round,
+         * and before the processor the round before settled on */
+        if (!(via_e <= R - skip[k] && via_e < s)) continue;
+        if (via_e <= R - skip[k + 1]) {          /* room to get closer from there */
+            if (c->onpath[e + 1]) c->st.anomalies++;
+            c->onpath[e + 1]++;
+            c->st.calls++;
+            k = allblocks(c, via_e, s, e, k, depth + 1);
+            c->onpath[e + 1]--;
         }
-        e = NEXT(c, e);
+        if (k >= q) {                            /* see above */
+            if (c->linked[e + 1]) c->st.anomalies++;
+            return k;
+        }
+        if (rp > R - skip[k + 1]) return k;      /* this call stands too far on for round k by now */
+        s = via_e;                               /* via_e is r'_k ... */
+        c->idx[k] = e;                           /* ... and e, the smallest index on the way there, its block */
+        k = k + 1;
+        unlink_index(c, e);
     }
     return k;
 }
@@ -209,32 +212,34 @@ static int sendschedule_sk(const int64_t *skip, int q, int64_t p, int64_t r,
     if (r == 0) {
         for (int k = 0; k < q; k++) send[k] = k;
     } else {
+        /* rp (r') is the rank within the range [0, e) that is still being
+         * halved, c the block the rank means to send */
         int b = baseblock_sk(skip, q, r);
         int64_t rp = r, e = p;
         int32_t c = b;
         for (int k = q - 1; k >= 1; k--) {
-            if (rp < skip[k]) {                                   /* lower part */
-                if (rp + skip[k] < e || e < skip[k - 1] || (k == 1 && b > 0)) {
-                    send[k] = c;
-                } else {                                          /* violation */
-                    recvschedule_sk(skip, q, p, (r + skip[k]) % p, block, NULL);
-                    send[k] = block[k];
-                    nviol++;
-                    vmask |= (uint32_t)1 << k;
-                }
-                if (e > skip[k]) e = skip[k];
-            } else {                                              /* upper part */
+            const int in_lower_half = rp < skip[k];
+            int known;                       /* does the structure say what the to-processor lacks? */
+            if (in_lower_half) {
+                /* keeps sending c as long as the to-processor is inside the
+                 * range, or the range is too small for it to have c */
+                known = rp + skip[k] < e || e < skip[k - 1] || (k == 1 && b > 0);
+            } else {
                 c = k - q;
-                if (k == 1 || rp > skip[k] || e - skip[k] < skip[k - 1]) {
-                    send[k] = c;
-                } else if (rp + skip[k] > e) {                    /* violation */
-                    recvschedule_sk(skip, q, p, (r + skip[k]) % p, block, NULL);
-                    send[k] = block[k];
-                    nviol++;
-                    vmask |= (uint32_t)1 << k;
-                } else {
-                    send[k] = c;
-                }
+                known = k == 1 || rp > skip[k] || e - skip[k] < skip[k - 1] ||
+                        !(rp + skip[k] > e);
+            }
+            if (known) {
+                send[k] = c;
+            } else {                         /* a violation: ask the to-processor's own schedule */
+                recvschedule_sk(skip, q, p, (r + skip[k]) % p, block, NULL);
+                send[k] = block[k];
+                nviol++;
+                vmask |= (uint32_t)1 << k;
+            }
+            if (in_lower_half) {
+                if (e > skip[k]) e = skip[k];
+            } else {
                 rp = rp - skip[k];
                 e = e - skip[k];
             }

@@ -1208,12 +1208,9 @@ int bcast_q(uint32_t p) { return host_q(p); }
 int bcast_skips(uint32_t p, uint32_t *skips, int *q_out) {
   const int q = host_q(p);
   if (q < 0 || !skips) return BCAST_EINVAL;
-  int k = q;
-  skips[k] = p;
-  while (k > 0) {                       // Algorithm 2
-    skips[k - 1] = skips[k] - skips[k] / 2u;
-    --k;
-  }
+  // Algorithm 2 halves with rounding up q - k times: skip[k] = ceil(p / 2^(q-k))
+  for (int k = 0; k < q; ++k) skips[k] = ((p - 1u) >> (q - k)) + 1u;
+  skips[q] = p;
   if (q_out) *q_out = q;
   return BCAST_OK;
 }

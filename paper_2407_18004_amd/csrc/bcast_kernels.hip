@@ -1119,6 +1119,24 @@ int persistent_grid(uint64_t n_blocks_wanted) {
   return (int)(g == 0 ? 1 : g);
 }
 
+// Grid of the kernels whose wavefronts work through runs of 64-rank tiles and carry records from
+// tile to tile: the first tile of a run has nothing to take over and costs about three times a
+// later one, so runs should be long, while several resident sets of workgroups are still needed
+// for the dispatcher to even out the load.  24 workgroups per CU (three resident sets) measured
+// best on MI355X: against 64, 2^26 ranks of p = 2^31 - 1 hash 3 % faster, of p = 2^30 + 1 10 %
+// faster, tables of 16 to 64 million ranks 2-4 % faster; 16 to 32 are level, 8 and 96 slower.
+constexpr uint64_t kRunGridPerCu = 24;
+int run_grid_cap() {
+  const int cap = persistent_grid(UINT64_MAX);                  // 64 workgroups per CU
+  return cap < 0 ? cap : (int)((uint64_t)cap / 64u * kRunGridPerCu);
+}
+int lone_grid(uint64_t n_blocks_wanted) {
+  const int cap = run_grid_cap();
+  if (cap < 0) return cap;
+  const uint64_t g = n_blocks_wanted < (uint64_t)cap ? n_blocks_wanted : (uint64_t)cap;
+  return (int)(g == 0 ? 1 : g);
+}
+
 bool launch_ok() { return hipGetLastError() == hipSuccess; }
 
 // Runs of tiles for a grid of `grid` workgroups (see RunSplit).
@@ -1169,14 +1187,15 @@ RunSplit split_runs(uint64_t n_tiles, int grid) {
 // than fit at once even out the load, because a SIMD serves its oldest
 // wavefront first and the young ones of a resident set fall behind by a factor
 // of two.  Measured on MI355X: about six tiles per wavefront is best for long
-// tables, two to four when that would leave fewer than two resident sets.  (A run is never
-// longer than 1.5 max(6, tiles / 65536) <= 768 tiles, so a row within a run fits 27 bits with
-// room to spare: the queue entries of the kernels rely on that.)
+// tables, two to four when that would leave fewer than two resident sets.  (With at most 2^25
+// tiles on 24,576 wavefronts and run lengths that differ by a factor of 1.5 from the mean, a run
+// stays below 2,100 tiles, so a row within a run fits 27 bits with room to spare: the queue
+// entries of the kernels rely on that.)
 constexpr uint64_t kRunTiles = 6;
 int run_grid(uint64_t n_tiles, uint32_t resident_per_cu) {
-  const int cap = persistent_grid(UINT64_MAX);                  // 64 workgroups per CU
+  const int cap = run_grid_cap();
   if (cap < 0) return -1;
-  const uint64_t one_set = (uint64_t)(cap / 64) * resident_per_cu;   // workgroups that fit at once
+  const uint64_t one_set = (uint64_t)cap / kRunGridPerCu * resident_per_cu;   // workgroups that fit at once
   const uint64_t per_wg = kWavesPerBlock;
   const uint64_t g_one = (n_tiles + per_wg - 1) / per_wg;        // one tile per wavefront
   if (g_one <= one_set) return (int)(g_one == 0 ? 1 : g_one);
@@ -1280,7 +1299,7 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
   }
   const uint64_t blocks = (n + kBlock - 1) / kBlock;
   const bool share = keep_next_tile(p);
-  const int grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : persistent_grid(blocks);
+  const int grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : lone_grid(blocks);
   if (grid < 0) return BCAST_EHIP;
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
   if (!prepare_table(p, q, n, workspace, (hipStream_t)stream, prm.table)) return BCAST_EHIP;
@@ -1324,7 +1343,7 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
   const bool work = n != 0 && !(edges && q == 0);
   int grid = 1;
   if (work) {
-    grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : persistent_grid((n + kBlock - 1) / kBlock);
+    grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : lone_grid((n + kBlock - 1) / kBlock);
     if (grid < 0) return BCAST_EHIP;
   } else if (persistent_grid(1) < 0) {
     return BCAST_EHIP;

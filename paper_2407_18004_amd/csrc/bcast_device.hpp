@@ -962,62 +962,171 @@ __device__ __forceinline__ uint32_t compute_rank(const Instance &in, uint32_t v,
   return flags | resolve_by_search(in, v, viol, send_row);
 }
 
-// Invariant flags (Conditions 3 and 4, first send, range) and the row hash of
-// one rank from its 2q bytes: row[0..q-1] = recvblock, row[q..2q-1] = sendblock.
+// Four (two) bytes of a row.  The kernels keep rows at 4-byte aligned addresses in LDS and read
+// them with aligned 4-byte loads wherever they can: loads from odd addresses, and wide loads from
+// addresses that are only 2-byte aligned, take several passes there (measured: reading rows of
+// 62 bytes packed back to back that way cost more than the byte loads it replaced).
+__device__ __forceinline__ uint32_t row_word(const int8_t *at) {
+  uint32_t w;
+  __builtin_memcpy(&w, at, 4);
+  return w;
+}
+__device__ __forceinline__ uint32_t row_half(const int8_t *at) {
+  uint16_t w;
+  __builtin_memcpy(&w, at, 2);
+  return w;
+}
+// Bytes shift .. shift + 3 (shift = 0..3) of the eight bytes lo, hi.
+__device__ __forceinline__ uint32_t bytes_from(uint32_t hi, uint32_t lo, uint32_t shift) {
+#ifdef BCAST_DEVICE_CODE_ON_HOST
+  return (uint32_t)((((uint64_t)hi << 32) | lo) >> (8u * (shift & 3u)));
+#else
+  return __builtin_amdgcn_alignbyte(hi, lo, shift);
+#endif
+}
+
+// Invariant flags of one rank from its 2q bytes, as they are defined, for any bytes at all:
+// row[0..q-1] = recvblock, row[q..2q-1] = sendblock.
+//   range:        an entry outside [-q, q-1];
+//   Condition 3:  the q receive entries are not, each once, {-q..-1} without b - q plus b
+//                 (the root: {-q..-1}); values v in range are bit v + q of a 64-bit set, and q
+//                 entries make the wanted set of q values only if they are distinct and in range;
+//   first send:   sendblock[0] is not b - q (the root: some sendblock[k] is not k);
+//   Condition 4:  some sendblock[k], k >= 1, of a rank other than the root is neither b - q nor
+//                 among recvblock[0..k-1].
+// The kernels get here for the root's wavefront only (see row_flags_clear), so the plain
+// quadratic form of Condition 4 is good enough.
+__device__ __forceinline__ uint32_t row_flags_entrywise(const Instance &in, uint32_t v, int b,
+                                                        const int8_t *row) {
+  const int q = (int)in.q;
+  const bool is_root = v == 0;
+  const int8_t *send = row + q;
+  bool out_of_range = false, recv_in_range = true;
+  uint64_t got = 0;
+  for (int k = 0; k < q; ++k) {
+    const int rv = row[k], sv = send[k];
+    const bool r_ok = rv >= -q && rv <= q - 1, s_ok = sv >= -q && sv <= q - 1;
+    out_of_range = out_of_range || !r_ok || !s_ok;
+    recv_in_range = recv_in_range && r_ok;
+    if (r_ok) got |= 1ull << (uint32_t)(rv + q);
+  }
+  const uint64_t negatives = (1ull << q) - 1ull;     // q <= 31
+  const uint64_t want = is_root ? negatives : ((negatives & ~(1ull << b)) | (1ull << (q + b)));
+  bool bad_s0 = false, bad_c4 = false;
+  if (is_root) {
+    for (int k = 0; k < q; ++k) bad_s0 = bad_s0 || (int)send[k] != k;
+  } else {
+    bad_s0 = q > 0 && (int)send[0] != b - q;
+    for (int k = 1; k < q; ++k) {
+      bool had = (int)send[k] == b - q;
+      for (int j = 0; j < k; ++j) had = had || row[j] == send[k];
+      bad_c4 = bad_c4 || !had;
+    }
+  }
+  return (recv_in_range && got == want ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
+         (bad_c4 ? BCAST_F_COND4 : 0u) | (out_of_range ? BCAST_F_RANGE : 0u);
+}
+
+// Whether all four flags of a rank other than the root are clear, with fewer operations than
+// the entry-by-entry form: true exactly when that form returns 0.
 //
-// Flags: values v in [-q, q-1] are bit v + q of a 64-bit set.  `seen` collects
-// recvblock[0..k-1]; Condition 3 holds iff after q entries it is exactly the
-// expected set, Condition 4 iff every sendblock[k], k >= 1, is in seen + {b - q}.
-// Hash: ten six-bit fields per word, in field order.
+// If every byte of the row is a six-bit value with its sign extended (bits 7..5 alike: one test
+// over the words of the row), a value is known by its low six bits, and those serve as the bit
+// number in the 64-bit set as they are: the shifts take their amount modulo 64.  The set starts
+// as {b - q}; a send entry of round k >= 1 must be in it when its round begins, a receive entry
+// joins it; in the end it must be {-q..-1} + {b}, q + 1 values.  The q receive entries can only
+// get it there by being distinct, in that set and none of them b - q (Condition 3, and in
+// range); a send entry found in the set is in range as well; sendblock[0] must be b - q.
+__device__ __forceinline__ bool row_flags_clear(uint32_t q, int b, const int8_t *row) {
+  const int8_t *send = row + q;
+  // the send part starts q bytes into the row: its words are cut from aligned ones
+  const int8_t *send_words = row + (q & ~3u);
+  const uint32_t cut = q & 3u;
+  uint64_t have = 1ull << ((uint32_t)(b - (int)q) & 63u);
+  uint32_t spread = 0;                               // bits 7 and 6 of a byte: b7 ^ b6, b6 ^ b5
+  // Round 0 needs no case of its own: sendblock[0] has to be b - q, which is in the set.
+  uint32_t in_have = 1u;
+  uint32_t k = 0;
+  uint32_t lo = q >= 4u ? row_word(send_words) : 0u;
+  for (; k + 4u <= q; k += 4u) {
+    const uint32_t hi = row_word(send_words + k + 4u);           // still inside the row's pitch
+    const uint32_t rw = row_word(row + k), sw = bytes_from(hi, lo, cut);
+    lo = hi;
+    spread |= (rw ^ (rw << 1)) | (sw ^ (sw << 1));
+    in_have &= (uint32_t)(have >> (sw & 63u));
+    have |= 1ull << (rw & 63u);
+    in_have &= (uint32_t)(have >> ((sw >> 8) & 63u));
+    have |= 1ull << ((rw >> 8) & 63u);
+    in_have &= (uint32_t)(have >> ((sw >> 16) & 63u));
+    have |= 1ull << ((rw >> 16) & 63u);
+    in_have &= (uint32_t)(have >> ((sw >> 24) & 63u));
+    have |= 1ull << ((rw >> 24) & 63u);
+  }
+  for (; k < q; ++k) {
+    const uint32_t rb = (uint32_t)(uint8_t)row[k], sb = (uint32_t)(uint8_t)send[k];
+    spread |= (rb ^ (rb << 1)) | (sb ^ (sb << 1));
+    in_have &= (uint32_t)(have >> (sb & 63u));
+    have |= 1ull << (rb & 63u);
+  }
+  const uint64_t negatives = ~0ull << (64u - q);     // the bits of -q..-1 (q >= 1)
+  return (spread & 0xC0C0C0C0u) == 0u && (in_have & 1u) != 0u && have == (negatives | (1ull << b)) &&
+         (int)send[0] == b - (int)q;
+}
+
+// 24 bits: the low six bits of the four bytes of w, bit 5 flipped ((x + 32) mod 64 for a byte x),
+// the first byte lowest.
+__device__ __forceinline__ uint32_t four_fields(uint32_t w) {
+  const uint32_t x = (w & 0x3F3F3F3Fu) ^ 0x20202020u;
+  const uint32_t y = (x & 0x003F003Fu) | ((x >> 2) & 0x0FC00FC0u);
+  return (y & 0xFFFu) | ((y >> 4) & 0xFFF000u);
+}
+
+// Bytes from one row to the next where digest_rank reads them: a multiple of four that holds the
+// 2q bytes of a row and the one aligned word that row_flags_clear reads past them when q is a
+// multiple of four, and an odd number of words, so that the 64 lanes of a wavefront reading the
+// same word of their rows hit different LDS banks.
+__host__ __device__ inline uint32_t digest_row_pitch(uint32_t q) { return 4u * (((2u * q + 3u) / 4u) | 1u); }
+
+// Invariant flags and row hash of one rank from its 2q bytes at a 4-byte aligned address, with
+// the bytes up to digest_row_pitch(q) readable.  The hash takes the entries as
+// six-bit fields (value + 32), ten to a 64-bit word in the order of the row, the last word
+// filled up with zero bits; here 20 fields, two words, come from five 4-byte reads.
 __device__ __forceinline__ void digest_rank(const Instance &in, uint32_t r, uint32_t v, int b,
                                             const int8_t *row, uint64_t &hash, uint32_t &flags) {
   const uint32_t q = in.q;
   const uint32_t two_q = 2u * q;
-  const bool is_root = v == 0;
-  // `have`: what the rank may send so far, b - q from the start (not for the root, which is not
-  // held to Condition 4), then every block it has received.  q receive entries fill it up to
-  // exactly {-q..-1} + {b} if and only if they are the set of Condition 3 (one entry too few of
-  // that set leaves a gap, since b - q itself is not among them).
-  uint64_t have = is_root ? 0ull : 1ull << b;
-  uint32_t u_max = 0, bad_c4 = 0;
-  for (uint32_t k = 0; k < q; ++k) {
-    const uint32_t ur = (uint32_t)((int)row[k] + (int)q);        // value + q: in range iff < 2q
-    const uint32_t us = (uint32_t)((int)row[q + k] + (int)q);
-    u_max = ur > u_max ? ur : u_max;
-    u_max = us > u_max ? us : u_max;
-    bad_c4 |= (uint32_t)(((have >> (us & 63u)) & 1ull) == 0ull && k != 0);  // round 0: send0
-    have |= 1ull << (ur & 63u);
+  const bool clear = q > 0 && v != 0 && row_flags_clear(q, b, row);
+  flags = 0;
+  if (__any(!clear)) {                               // the root's wavefront, and q = 0
+    if (!clear) flags = row_flags_entrywise(in, v, b, row);
   }
-  bad_c4 = is_root ? 0u : bad_c4;
-  // sendblock[0] is b - q by Condition 4 (value + q = b); the root sends block k in round k
-  bool bad_s0 = !is_root && q > 0 && (uint32_t)((int)row[q] + (int)q) != (uint32_t)b;
-  if (__any(is_root)) {
-    if (is_root)
-      for (uint32_t k = 0; k < q; ++k) bad_s0 = bad_s0 || (int)row[q + k] != (int)k;
-  }
-  const bool bad_range = u_max >= two_q && q > 0;
-  const uint64_t low = q >= 32 ? 0xFFFFFFFFull : ((1ull << q) - 1ull);
-  const uint64_t want = is_root ? low : (low | (1ull << (q + (uint32_t)b)));
-  flags = (have == want && !bad_range ? 0u : BCAST_F_COND3) | (bad_s0 ? BCAST_F_SEND0 : 0u) |
-          (bad_c4 ? BCAST_F_COND4 : 0u) | (bad_range ? BCAST_F_RANGE : 0u);
 
-  // ten six-bit fields per word; full words first, then the tail
   uint64_t h = sm64(((uint64_t)in.p << 32) ^ (uint64_t)r);
   uint32_t f0 = 0;
-  for (; f0 + 10u <= two_q; f0 += 10u) {
-    uint32_t lo = 0, hi = 0;
-#pragma unroll
-    for (uint32_t t = 0; t < 5; ++t) {
-      lo |= (((uint32_t)(int)row[f0 + t] + 32u) & 63u) << (6u * t);
-      hi |= (((uint32_t)(int)row[f0 + 5u + t] + 32u) & 63u) << (6u * t);
-    }
-    h = sm64(h ^ ((uint64_t)lo | ((uint64_t)hi << 30)));
+  for (; f0 + 20u <= two_q; f0 += 20u) {
+    const uint64_t c0 = four_fields(row_word(row + f0)), c1 = four_fields(row_word(row + f0 + 4u));
+    const uint64_t c2 = four_fields(row_word(row + f0 + 8u)), c3 = four_fields(row_word(row + f0 + 12u));
+    const uint64_t c4 = four_fields(row_word(row + f0 + 16u));
+    h = sm64(h ^ (c0 | (c1 << 24) | ((c2 & 0xFFFull) << 48)));
+    h = sm64(h ^ ((c2 >> 12) | (c3 << 12) | (c4 << 36)));
   }
-  if (f0 < two_q) {
-    uint64_t w = 0;
-    for (uint32_t t = 0; f0 + t < two_q; ++t)
-      w |= (uint64_t)(((uint32_t)(int)row[f0 + t] + 32u) & 63u) << (6u * t);
-    h = sm64(h ^ w);
+  if (f0 < two_q) {                                  // an even number of fields, 2 to 18, is left
+    const uint32_t rem = two_q - f0;
+    uint64_t c[5];
+#pragma unroll
+    for (uint32_t j = 0; j < 5; ++j) {
+      uint32_t w = 0;
+      if (4u * j + 4u <= rem) w = row_word(row + f0 + 4u * j);
+      else if (4u * j + 2u <= rem) w = row_half(row + f0 + 4u * j);
+      c[j] = four_fields(w);
+    }
+    // fields past the end of the row are zero bits in the word
+    const uint64_t m0 = rem >= 10u ? ~0ull >> 4 : (1ull << (6u * rem)) - 1ull;
+    h = sm64(h ^ ((c[0] | (c[1] << 24) | ((c[2] & 0xFFFull) << 48)) & m0));
+    if (rem > 10u) {
+      const uint64_t m1 = (1ull << (6u * (rem - 10u))) - 1ull;
+      h = sm64(h ^ (((c[2] >> 12) | (c[3] << 12) | (c[4] << 36)) & m1));
+    }
   }
   hash = h;
 }

@@ -201,6 +201,15 @@ constexpr uint32_t kQueueWords = kDeferCap > kRowQueueCap ? kDeferCap : kRowQueu
 __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
   return slice_words(q) + 16u * q + kQueueWords + kRecordWords;
 }
+// The same for k_digest, whose rows never leave LDS and are laid out for word reads: 64 rows
+// digest_row_pitch(q) bytes apart.
+__host__ __device__ inline uint32_t digest_slice_words(uint32_t q) { return 16u * digest_row_pitch(q); }
+__host__ __device__ inline uint32_t digest_lone_block_words(uint32_t q) {
+  return kWavesPerBlock * (digest_slice_words(q) + kRecordWords);
+}
+__host__ __device__ inline uint32_t digest_deferred_wave_words(uint32_t q) {
+  return digest_slice_words(q) + 16u * q + kQueueWords + kRecordWords;
+}
 
 // Hands n entries (one per lane with `mine`, as row of the launch << 5 | round) to the list that
 // k_fill_open works off after this kernel, if there is a list and it has room for all of them.
@@ -478,10 +487,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const Instance in = make_instance(prm.p, prm.q, prm.root);
   const uint32_t q = prm.q;
-  const uint32_t slice_w = slice_words(q);
-  uint32_t *words = lds_dyn + wave * (kShare ? deferred_wave_words(q) : slice_w);
+  const uint32_t pitch = digest_row_pitch(q);
+  const uint32_t slice_w = digest_slice_words(q);
+  uint32_t *words = lds_dyn + wave * (kShare ? digest_deferred_wave_words(q) : slice_w);
   int8_t *tile_recv = reinterpret_cast<int8_t *>(words);
-  int8_t *recv_row = tile_recv + lane * 2u * q;
+  int8_t *recv_row = tile_recv + lane * pitch;
   int8_t *send_row = recv_row + q;
   const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
@@ -506,7 +516,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
-                                            2u * q, q, lane, wave, record, long_run, prm.table);
+                                            pitch, q, lane, wave, record, long_run, prm.table);
       acc_flags |= st.flags;
       if (lane < st.n_valid) take_row((uint32_t)(prm.r_begin + tile * kWave + lane), st.v, st.b);
       wave_lds_sync();                         // the slice is rewritten next
@@ -553,7 +563,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
           acc_flags |= resolve_by_search(in, v, viol, send_row);
         } else {
           open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
-                                    2u * q, q, lane, n_here, n_valid_above);
+                                    pitch, q, lane, n_here, n_valid_above);
           if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
         }
         if (open == 0) take_row(r, v, b);
@@ -1360,8 +1370,8 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
   if (!prepare_table(p, q, n, workspace, st, prm.table)) return BCAST_EHIP;
   const bool memo = prm.table.entries != nullptr;
-  const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
-                           : (size_t)lone_block_words(prm.q) * 4u;
+  const size_t lds = share ? (size_t)kWavesPerBlock * digest_deferred_wave_words(prm.q) * 4u
+                           : (size_t)digest_lone_block_words(prm.q) * 4u;
   const dim3 g(grid), b(kBlock);
 #define BCAST_LAUNCH_DIGEST(S, E, M) hipLaunchKernelGGL((k_digest<S, E, M>), g, b, lds, st, prm)
   if (share) {

@@ -130,7 +130,7 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
   for (uint64_t i = 0; i < m; ++i) {
-    int8_t buf[64];
+    alignas(4) int8_t buf[72];              // rows are read by aligned words, a little past 2q bytes
     memset(buf, 0x55, sizeof buf);
     int b = 0;
     const uint32_t v = virtual_rank(in, ranks[i]);
@@ -188,7 +188,8 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   }
   // one slice that is reused (rows of the previous tile stay where they are until they are
   // overwritten) and a copy of the receive rows of the tile above
-  static int8_t tile[64 * 62];
+  alignas(4) static int8_t tile[64 * 68];      // rows digest_row_pitch(q) apart, as k_digest keeps them
+  const uint32_t pitch = digest_row_pitch(q);
   static int8_t above[64 * 31];
   static LockstepCache caches[64];            // D, M, top_v are per lane ...
   static uint32_t record_mem[kRecordWords];   // ... the rest is the wavefront's
@@ -215,18 +216,18 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
       shim_wave::run((int)n_valid, [&](int lane) {
         vr[lane] = virtual_rank(in, (uint32_t)(r_begin + row0 + lane));
         if (table.entries)
-          viol[lane] = compute_rank_phase1<true>(in, vr[lane], tile + lane * 2 * q,
-                                                 tile + lane * 2 * q + q, b[lane], fl[lane],
+          viol[lane] = compute_rank_phase1<true>(in, vr[lane], tile + lane * pitch,
+                                                 tile + lane * pitch + q, b[lane], fl[lane],
                                                  caches[lane], long_run && n_valid == 64, table, memo[lane]);
         else
-          viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * 2 * q,
-                                           tile + lane * 2 * q + q, b[lane], fl[lane],
+          viol[lane] = compute_rank_phase1(in, vr[lane], tile + lane * pitch,
+                                           tile + lane * pitch + q, b[lane], fl[lane],
                                            caches[lane], long_run && n_valid == 64);
       });
       for (uint32_t lane = 0; lane < n_valid; ++lane) {
-        int8_t *recv_row = tile + lane * 2 * q;
+        int8_t *recv_row = tile + lane * pitch;
         uint32_t open = resolve_from_tiles(in, viol[lane], recv_row + q, tile, next_recv,
-                                           2 * q, q, lane, n_valid, n_valid_next);
+                                           pitch, q, lane, n_valid, n_valid_next);
         borrowed += (uint64_t)__popc(viol[lane] ^ open);
         if (table.entries) {
           const uint32_t left = resolve_from_table(in, table, vr[lane], memo[lane], open, recv_row + q);
@@ -238,7 +239,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
       }
       for (uint32_t lane = 0; lane < n_valid; ++lane) {
         const uint64_t i = row0 + lane;
-        const int8_t *recv_row = tile + lane * 2 * q;
+        const int8_t *recv_row = tile + lane * pitch;
         for (uint32_t k = 0; k < 2 * q; ++k) rows[i * 2 * q + k] = recv_row[k];
         uint64_t h = 0;
         uint32_t fl2 = 0;
@@ -288,7 +289,7 @@ void shim_edge_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row, ui
                    uint64_t *xs) {
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
-  int8_t buf[64];
+  alignas(4) int8_t buf[72] = {0};
   for (uint32_t k = 0; k < 2 * q; ++k) buf[k] = (int8_t)row[k];
   edge_rank(in, r, buf, *xr, *xs);
 }
@@ -298,7 +299,7 @@ void shim_digest_row(uint32_t p, uint32_t root, uint32_t r, const int32_t *row,
                      uint64_t *hash, uint32_t *flags) {
   const uint32_t q = q_of(p);
   const Instance in = make_instance(p, q, root);
-  int8_t buf[64];
+  alignas(4) int8_t buf[72] = {0};
   for (uint32_t k = 0; k < 2 * q; ++k) buf[k] = (int8_t)row[k];
   const uint32_t v = virtual_rank(in, r);
   const int b = (int)q - (int)baseblock_level(in.pm1, q, v);

@@ -137,7 +137,15 @@ def test_flags_on_planted_mistakes(shim):
         for trial in range(12):
             bad = row.copy()
             pos = int(rng.integers(0, 2 * q))
-            bad[pos] = int(rng.integers(-q, q))
+            # values of the legal range, any byte, and the bytes that agree with the right value
+            # in their low six bits (the quick test of a row knows a value by those)
+            if trial % 4 == 0:
+                bad[pos] = int(rng.integers(-128, 128))
+            elif trial % 4 == 1:
+                bad[pos] = int(row[pos]) + (64 if row[pos] < 0 or trial % 8 == 1 else -64)
+                assert -128 <= bad[pos] <= 127
+            else:
+                bad[pos] = int(rng.integers(-q, q))
             want = oracle.digest_row(p, root, r, bad[:q], bad[q:])
             h = ctypes.c_uint64(0)
             fl = ctypes.c_uint32(0)

@@ -340,8 +340,11 @@ enum RecordWord : uint32_t {
   kTopT, kTopTw,                    // v - rem and v - W after them
   kTopJb, kTopPathr, kTopE, kTopViol, kTopBits, kTopC,   // bits: closed, anom
   kTopMargin, kTopReplays,
+  kRecRowsHeld,                     // the wavefront's rows still hold the record's accepts, see ascent_run
+  kRecRoundOfB,                     // the round in which the stretch accepts level 0 (block b), or none
   kRecordWords = 32
 };
+constexpr uint32_t kNoRound = 0xFFFFFFFFu;
 
 struct LockstepCache {
   uint32_t *mem;
@@ -354,6 +357,7 @@ __device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *
   c.D = 0; c.M = 0; c.top_v = 0;
   if (mem != nullptr) {
     mem[kRecValid] = 0; mem[kRecReplays] = 0; mem[kTopValid] = 0; mem[kTopReplays] = 0;
+    mem[kRecRowsHeld] = 0;
   }
 }
 
@@ -388,7 +392,11 @@ __device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *
 //    round) instead of running the loop.  The same bound, applied to the
 //    differences between the lanes of the recording tile, shows that its lanes
 //    did make the same moves.  `use_cache` = false: no replay; when it is true,
-//    all lanes of the wavefront must be in the call.
+//    all lanes of the wavefront must be in the call, and every lane must pass the
+//    same row to `emit` from tile to tile: the accepts of the stretch are minus the
+//    level in every lane (only block b, for level 0, is the lane's own), so a tile
+//    that takes the record over while the rows still hold them from the tile
+//    before writes nothing but that one entry.
 //
 // The descent is made by the caller (top_down_level, together with Algorithms 3
 // and 6, which walk over the same levels): W, pathr and anom_in are its result.
@@ -497,7 +505,10 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
       see(D, sk1);
       if (D >= sk1) {                       // accept e for round k
         emit(k, jj == 0 ? b : -(int)jj);
-        if (kTrack) reinterpret_cast<uint8_t *>(cache.mem)[k] = (uint8_t)jj;
+        if (kTrack) {
+          reinterpret_cast<uint8_t *>(cache.mem)[k] = (uint8_t)jj;
+          if (jj == 0u) cache.mem[kRecRoundOfB] = k;
+        }
         live ^= 1u << jj;
         see(sk1, t + 2u);
         M = sk1 > t + 1u ? sk1 : t + 1u;
@@ -559,9 +570,15 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
         const bool ok = dD == dD0 && dM == dM0 && far <= cache.mem[kRecMargin] &&
                         it + cache.mem[kRecIters] <= cap;
         if (!__any(!ok)) {
-          for (uint32_t kk = k0; kk < q; ++kk) {
-            const uint32_t jj = reinterpret_cast<const uint8_t *>(cache.mem)[kk];
-            emit(kk, jj == 0 ? b : -(int)jj);
+          if (cache.mem[kRecRowsHeld] != 0u) {
+            const uint32_t kb = cache.mem[kRecRoundOfB];
+            if (kb != kNoRound) emit(kb, b);
+          } else {
+            for (uint32_t kk = k0; kk < q; ++kk) {
+              const uint32_t jj = reinterpret_cast<const uint8_t *>(cache.mem)[kk];
+              emit(kk, jj == 0 ? b : -(int)jj);
+            }
+            cache.mem[kRecRowsHeld] = 1u;
           }
           k = q;
           it += cache.mem[kRecIters];
@@ -573,7 +590,10 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
       record = !replayed;
     }
   }
+  // rows written by anything but this record's own accepts no longer hold them
+  if (!replayed && cache.mem != nullptr) cache.mem[kRecRowsHeld] = 0u;
   if (record) {
+    cache.mem[kRecRoundOfB] = kNoRound;
     for (; it < cap && go; ++it) move(TrackOn{});
     // usable if it ran to the end without incident and no lane can have left the others
     const uint32_t apart = stretch_shift(D_in - lane0_of(D_in), M_in - lane0_of(M_in));
@@ -585,6 +605,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
     cache.D = D_in; cache.M = M_in;
     cache.mem[kRecMargin] = m_all;
     cache.mem[kRecIters] = it - it_in;
+    cache.mem[kRecRowsHeld] = cache.mem[kRecValid];    // all 64 rows were written by the stretch just now
   } else {
     for (; it < cap && go; ++it) move(TrackOff{});
   }

@@ -755,6 +755,29 @@ def test_calls_with_workspace_equal_the_oracle(p, root, a, n):
         assert np.array_equal(recv.cpu().numpy(), want[:, :q]) and np.array_equal(send.cpu().numpy(), want[:, q:])
 
 
+@pytest.mark.parametrize("q", list(range(2, 32)))
+def test_digest_and_edge_check_for_every_number_of_rounds(q):
+    """Every q: the row layout of the digest kernels, the words they read rows by and the tail of
+    the hash change with q (q mod 4, 2q mod 20); p = 2^q - 1, 2^q and an odd p with violations."""
+    odd = (1 << (q - 1)) + 1 + 2 * ((q * 2654435761) % max(1, 1 << max(q - 3, 0)))
+    for p in (2**q - 1, 2**q, odd):
+        if p > workloads.STREAMED_P:                   # 2^31 is past the largest p of the library
+            continue
+        assert lib.bcast_q(p) == q, (p, q)
+        n = min(p, 150_000)
+        root = (p * 5) // 7
+        a = max(0, min(root - n // 3, p - n))          # the root inside the range
+        assert gpu_digest(p, root, a, a + n) == oracle.digest(p, root, a, a + n, send_mode=1), (p, "digest")
+        assert gpu_edgecheck(p, root, a, a + n) == oracle.edgecheck(p, root, a, a + n, send_mode=1), (p, "edges")
+        if p >= 2**21 + 70_000:                        # with the table of deep entries and records in use
+            n = 2**21 + 4321
+            a = max(0, min(root - n // 3, p - n))
+            ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+            dg, xs = ws_digest_and_edges(p, root, a, a + n, ws)
+            assert dg == oracle.digest(p, root, a, a + n, send_mode=1), (p, "digest, workspace")
+            assert xs == oracle.edgecheck(p, root, a, a + n, send_mode=1), (p, "edges, workspace")
+
+
 def test_calls_with_workspace_on_the_streamed_instance():
     p = workloads.STREAMED_P
     gold = streamed_golden()

@@ -293,12 +293,13 @@ __device__ __forceinline__ uint32_t first_level_taken(uint32_t pm1, uint32_t v) 
   return jt == 0u ? 1u : jt;
 }
 
-// Number of levels at the top whose skip is at least kTopSkip (levels 1 .. n).
+// Number of levels at the top whose skip is at least min_skip (levels 1 .. n).
 constexpr uint32_t kTopSkip = 4096u;
-__device__ __forceinline__ uint32_t top_level_count(uint32_t pm1, uint32_t q) {
-  if (pm1 < kTopSkip) return 0u;
-  // skip_at_level(j) >= kTopSkip  <=>  (pm1 >> j) >= kTopSkip - 1
-  uint32_t n = 32u - (uint32_t)__clz((int)(pm1 / (kTopSkip - 1u)));   // first j with pm1 >> j < kTopSkip - 1
+constexpr uint32_t kUpperSkip = 65536u;
+__device__ __forceinline__ uint32_t top_level_count(uint32_t pm1, uint32_t q, uint32_t min_skip = kTopSkip) {
+  if (pm1 < min_skip) return 0u;
+  // skip_at_level(j) >= min_skip  <=>  (pm1 >> j) >= min_skip - 1
+  uint32_t n = 32u - (uint32_t)__clz((int)(pm1 / (min_skip - 1u)));   // first j with pm1 >> j < min_skip - 1
   n = n == 0u ? 0u : n - 1u;
   return n < q ? n : q;
 }
@@ -342,7 +343,10 @@ enum RecordWord : uint32_t {
   kTopMargin, kTopReplays,
   kRecRowsHeld,                     // the wavefront's rows still hold the record's accepts, see ascent_run
   kRecRoundOfB,                     // the round in which the stretch accepts level 0 (block b), or none
-  kRecordWords = 32
+  // the uppermost of the top levels (skips of kUpperSkip and more) once more, as a record of their own
+  kUpValid, kUpLevels, kUpV0,       // valid, how many, the first lane's v when they were recorded
+  kUpT, kUpTw, kUpJb, kUpPathr, kUpE, kUpViol, kUpBits, kUpC, kUpMargin,
+  kRecordWords = 48
 };
 constexpr uint32_t kNoRound = 0xFFFFFFFFu;
 
@@ -350,15 +354,24 @@ struct LockstepCache {
   uint32_t *mem;
   uint32_t D, M;                    // this lane's D and M on entry to the recorded stretch
   uint32_t top_v;                   // this lane's v when the top levels were recorded
+  uint32_t lane;                    // this lane's number in the wavefront
 };
 
-__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *mem) {
+// mem: kRecordWords words of the wavefront's own, or null for a rank on its own (no records).
+__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *mem, uint32_t lane = 0u) {
   c.mem = mem;
   c.D = 0; c.M = 0; c.top_v = 0;
+  c.lane = lane;
   if (mem != nullptr) {
     mem[kRecValid] = 0; mem[kRecReplays] = 0; mem[kTopValid] = 0; mem[kTopReplays] = 0;
-    mem[kRecRowsHeld] = 0;
+    mem[kRecRowsHeld] = 0; mem[kUpValid] = 0;
   }
+}
+
+// The wavefront's rows have been written by something other than its tiles (or are about to be):
+// nothing that relies on entries staying in them from tile to tile may be taken over.
+__device__ __forceinline__ void lockstep_cache_rows_lost(LockstepCache &c) {
+  c.mem[kTopValid] = 0; c.mem[kUpValid] = 0; c.mem[kRecRowsHeld] = 0;
 }
 
 // The receive search again, in the form the kernels use: same state and same
@@ -768,6 +781,46 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       if (kMemo) margin_own = cache.mem[kTopMargin] - away;     // >= 1: what is left of the margin
     } else {
       uint32_t margin = 0xFFFFFFFFu;
+      // The decisions that flip from one tile to the next are nearly always those at the smaller
+      // of these skips: the levels with skips of kUpperSkip and more are recorded once more on
+      // their own, and a tile that cannot take all the top levels over usually still takes those
+      // (their rounds of Algorithm 6 are in the rows from the tile that recorded them).  The lanes
+      // of such a tile hold consecutive v, so the first lane's v stands for all of them.
+      const uint32_t n_up = top_level_count(in.pm1, q, kUpperSkip);
+      if (n_up >= 4u && n_up < n_top) {
+        const uint32_t v0 = lane0_of(v);
+        const bool in_a_row = v - cache.lane == v0;
+        const uint32_t away_up = abs_difference(v0, cache.mem[kUpV0]);
+        const bool near_up = cache.mem[kUpValid] != 0u && cache.mem[kUpLevels] == n_up && in_a_row &&
+                             away_up + 1u <= cache.mem[kUpMargin];
+        if (!__any(!near_up)) {
+          s.rem = v - cache.mem[kUpT];
+          s.W = (int)(v - cache.mem[kUpTw]);
+          s.jb = cache.mem[kUpJb]; s.pathr = cache.mem[kUpPathr]; s.e = cache.mem[kUpE]; s.c = (int)cache.mem[kUpC];
+          s.viol = cache.mem[kUpViol];
+          s.closed = (cache.mem[kUpBits] & 1u) != 0u;
+          s.anom = cache.mem[kUpBits] >> 1;
+          margin = cache.mem[kUpMargin] - away_up;                // >= 1: what is left of their margin
+        } else {
+          for (; j <= n_up; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
+          const uint32_t T = v - s.rem, Tw = v - (uint32_t)s.W;
+          const uint32_t bits = (uint32_t)s.closed | (s.anom << 1);
+          const uint32_t T0 = lane0_of(T), Tw0 = lane0_of(Tw), jb0 = lane0_of(s.jb), pathr0 = lane0_of(s.pathr),
+                         e0 = lane0_of(s.e), c0 = lane0_of((uint32_t)s.c), viol0 = lane0_of(s.viol),
+                         bits0 = lane0_of(bits);
+          const bool same = in_a_row && T == T0 && Tw == Tw0 && s.jb == jb0 && s.pathr == pathr0 && s.e == e0 &&
+                            (uint32_t)s.c == c0 && s.viol == viol0 && bits == bits0;
+          cache.mem[kUpValid] = (uint32_t)!__any(!same);
+          cache.mem[kUpLevels] = n_up;
+          cache.mem[kUpV0] = v0;
+          cache.mem[kUpT] = T0; cache.mem[kUpTw] = Tw0; cache.mem[kUpJb] = jb0;
+          cache.mem[kUpPathr] = pathr0; cache.mem[kUpE] = e0;
+          cache.mem[kUpC] = c0; cache.mem[kUpViol] = viol0;
+          cache.mem[kUpBits] = bits0;
+          cache.mem[kUpMargin] = wave_min32(margin);
+        }
+        j = n_up + 1u;
+      }
       for (; j <= n_top; ++j) top_down_level<true, true>(in.pm1, q, j, s, margin, put_send);
       const uint32_t T = v - s.rem, Tw = v - (uint32_t)s.W;
       const uint32_t bits = (uint32_t)s.closed | (s.anom << 1);

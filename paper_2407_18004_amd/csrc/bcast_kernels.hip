@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;     // recording costs more than it saves on two tiles
   if (!kShare) {
-    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
                                             pitch, send_off, lane, wave, record, long_run, prm.table);
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
   uint32_t *queue = words + slice_w + 16u * q;
-  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords);
+  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane);
   const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
@@ -513,7 +513,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;
   if (!kShare) {
-    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords);
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
                                             pitch, q, lane, wave, record, long_run, prm.table);
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   } else {
     int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
     uint32_t *queue = words + slice_w + 16u * q;
-    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords);
+    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane);
     const uint64_t run_row0 = t_lo * kWave;
     uint32_t n_queued = 0;                     // the same in all lanes; at most 63 between tiles
     uint32_t n_valid_above = 0;
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       }
       if (batch) {
         n_queued -= n_here;
-        record.mem[kTopValid] = 0;             // the rows of the last tile are gone
+        lockstep_cache_rows_lost(record);      // the rows of the last tile are gone
       } else {
         const uint64_t who = __ballot(open != 0);
         const uint32_t slot = n_queued + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));

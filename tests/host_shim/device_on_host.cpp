@@ -202,7 +202,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   for (uint64_t run0 = 0; run0 < n_tiles; run0 += per_run) {
     const uint64_t run1 = run0 + per_run < n_tiles ? run0 + per_run : n_tiles;
     memset(tile, 0x55, sizeof tile);
-    for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem);
+    for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem, (uint32_t)l);
     const bool long_run = run1 - run0 >= 3;   // as in the kernels
     uint32_t n_valid_next = 0;
     const int8_t *next_recv = nullptr;

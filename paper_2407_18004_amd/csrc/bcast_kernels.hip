@@ -53,7 +53,8 @@ __device__ __forceinline__ int widen(int byte_val) {
   return byte_val;
 }
 
-template <bool kMarkInvalid>
+// kStream: the 16-byte stores are marked non-temporal.
+template <bool kMarkInvalid, bool kStream = false>
 __device__ __forceinline__ void tile_out(const uint32_t *lds_words, int32_t *dst,
                                          uint32_t n_bytes, uint32_t lane) {
   const uint32_t groups = n_bytes >> 2;
@@ -67,7 +68,14 @@ __device__ __forceinline__ void tile_out(const uint32_t *lds_words, int32_t *dst
       o.y = widen<kMarkInvalid>((int)(int8_t)((w >> 8) & 0xFF));
       o.z = widen<kMarkInvalid>((int)(int8_t)((w >> 16) & 0xFF));
       o.w = widen<kMarkInvalid>((int)(int8_t)(w >> 24));
-      dst4[g] = o;
+      if (kStream) {
+        __builtin_nontemporal_store(o.x, &dst[4u * g]);
+        __builtin_nontemporal_store(o.y, &dst[4u * g + 1u]);
+        __builtin_nontemporal_store(o.z, &dst[4u * g + 2u]);
+        __builtin_nontemporal_store(o.w, &dst[4u * g + 3u]);
+      } else {
+        dst4[g] = o;
+      }
     }
   } else {
     for (uint32_t i = lane; i < (groups << 2); i += kWave)
@@ -269,10 +277,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   auto copy_out = [&](uint64_t row0, uint32_t n_valid) {
     if (prm.layout == kInterleaved) {
-      tile_out<false>(words, prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
+      tile_out<false, kShare>(words, prm.recv + row0 * 2u * q, n_valid * 2u * q, lane);
     } else if (prm.layout == kSeparate) {
-      tile_out<false>(words, prm.recv + row0 * q, n_valid * q, lane);
-      tile_out<false>(words + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
+      tile_out<false, kShare>(words, prm.recv + row0 * q, n_valid * q, lane);
+      tile_out<false, kShare>(words + (kWave * q) / 4, prm.send + row0 * q, n_valid * q, lane);
     } else if (lane < n_valid) {
       int32_t *rr = prm.recv + (row0 + lane) * (uint64_t)prm.ld;
       int32_t *sr = prm.send + (row0 + lane) * (uint64_t)prm.ld;

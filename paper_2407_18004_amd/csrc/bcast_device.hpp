@@ -662,14 +662,20 @@ __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32
 // walk through the rounds.
 // rho < 2 (the baseblock's level lies above, or the descent has ended there) has no entry: such
 // ranks take the levels one by one.
+//
+// Ranks that arrive with a smaller e (a quarter with S - 1, an eighth with S - 2, ...; never less
+// than S minus the number of levels above) find the violations of their deep rounds in a second
+// table, one 16-bit word per (S - e, rho): bit 15 valid, bits 0-10 as in w above.
 struct DeepTable {
   const uint4 *entries;             // kDeepMaxEntries of them, or null
+  const uint16_t *viol_by_e;        // [kDeepEs][kDeepMaxEntries], row S - e (row 0 is not used), or null
   uint32_t first_deep;              // first deep level (>= 5 when the table is in use)
   uint32_t n_rho;                   // S: entries exist for rho < S
 };
 
 constexpr uint32_t kDeepMaxEntries = 2u * kLockstepSkip + 2u;   // S <= 2 kLockstepSkip + 1
 constexpr uint32_t kDeepMinUpperLevels = 4u;
+constexpr uint32_t kDeepEs = 32u;                               // S - e < kDeepEs has a row
 
 __device__ __forceinline__ uint32_t deep_table_rhos(uint32_t pm1, uint32_t first_deep) {
   return first_deep >= 1u ? skip_at_level(pm1, first_deep - 1u) : 0u;
@@ -719,6 +725,22 @@ __device__ __forceinline__ uint4 deep_entry_build(uint32_t pm1, uint32_t q, uint
   e.y = a.D | (a.M << 16);
   e.z = lv_lo; e.w = lv_hi | (s.viol << 16);
   return e;
+}
+
+// The violations of Algorithm 6 in the deep rounds of a rank that arrives at the deep levels with
+// remainder rho and e = S - less, as a word of the second table: the same walk as the rank's own.
+__device__ __forceinline__ uint16_t deep_viol_build(uint32_t pm1, uint32_t q, uint32_t first_deep,
+                                                    uint32_t rho, uint32_t less) {
+  const uint32_t S = deep_table_rhos(pm1, first_deep);
+  if (rho < 2u || less >= S) return 0;
+  TopDown s;
+  s.rem = rho; s.jb = 0; s.closed = false;
+  s.W = 0; s.pathr = 0; s.anom = 0; s.c = 0; s.viol = 0;
+  s.e = S - less;
+  uint32_t unused = 0;
+  for (uint32_t j = first_deep; j <= q; ++j)
+    top_down_level<true, false, false>(pm1, q, j, s, unused, [](uint32_t, int) {});
+  return s.viol < 2048u ? (uint16_t)(s.viol | 0x8000u) : (uint16_t)0;
 }
 
 // Phase one of a rank: baseblock, receive schedule, send walk.  Writes
@@ -867,9 +889,15 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
     AscentState a;
     if (generic) {
       // the descent and Algorithm 3's baseblock come from the entry, and so do the deep rounds
-      // of Algorithm 6 if the rank arrives with e = S; otherwise Algorithm 6 walks through them
+      // of Algorithm 6: what they send follows from the levels taken, their violations are in the
+      // entry for a rank that arrives with e = S and in the second table for a smaller e
+      // (Algorithm 6 walks through them if there is no such word)
       const uint32_t fd = table.first_deep;
-      if (s.e == table.n_rho) {
+      const uint32_t less = table.n_rho - s.e;                             // e <= S
+      uint32_t deep_viol = 0x8000u | ((e.w >> 16) & 0x7FFu);
+      if (less != 0u)
+        deep_viol = less < kDeepEs && table.viol_by_e != nullptr ? table.viol_by_e[less * kDeepMaxEntries + rho] : 0u;
+      if ((deep_viol & 0x8000u) != 0u) {
         const uint32_t taken = (e.x >> 19) & 0x7FFu;
         for (; j < q; ++j) {
           const uint32_t upto = taken & ((2u << (j - fd)) - 1u);         // levels taken so far
@@ -877,7 +905,7 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
           s.c = upto != 0u ? -last : s.c;
           send_row[q - j] = (int8_t)s.c;
         }
-        s.viol = (s.viol << (q - fd)) | ((e.w >> 16) & 0x7FFu);
+        s.viol = (s.viol << (q - fd)) | (deep_viol & 0x7FFu);
       } else {
         for (; j <= q; ++j) top_down_level<true, false, false>(in.pm1, q, j, s, unused, put_send);
       }
@@ -926,7 +954,7 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
                                                         int &b_out, uint32_t &flags,
                                                         LockstepCache &cache, bool use_cache) {
   DeepTable none;
-  none.entries = nullptr; none.first_deep = 0; none.n_rho = 0;
+  none.entries = nullptr; none.viol_by_e = nullptr; none.first_deep = 0; none.n_rho = 0;
   MemoOut unused;
   return compute_rank_phase1<false>(in, v, recv_row, send_row, b_out, flags, cache, use_cache, none, unused);
 }

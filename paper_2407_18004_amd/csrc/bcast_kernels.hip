@@ -607,11 +607,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
 // ------------------------------------------------- table of deep entries
 
-// One lane per rho (see DeepTable in the device header).
-__global__ __launch_bounds__(kBlock) void k_deep_table(uint4 *entries, uint32_t p, uint32_t q,
-                                                       uint32_t first_deep, uint32_t n_rho) {
-  const uint32_t rho = blockIdx.x * kBlock + threadIdx.x;
-  if (rho < n_rho) entries[rho] = deep_entry_build(p - 1u, q, first_deep, rho);
+// One lane per rho for the entries (the first blocks_per_row workgroups), then one lane per
+// (S - e, rho) for the second table (see DeepTable in the device header).
+__global__ __launch_bounds__(kBlock) void k_deep_table(uint4 *entries, uint16_t *viol_by_e, uint32_t p,
+                                                       uint32_t q, uint32_t first_deep, uint32_t n_rho,
+                                                       uint32_t blocks_per_row) {
+  const uint32_t row = blockIdx.x / blocks_per_row;            // 0: entries; 1 .. kDeepEs - 1: S - e
+  const uint32_t rho = (blockIdx.x - row * blocks_per_row) * kBlock + threadIdx.x;
+  if (rho >= n_rho) return;
+  if (row == 0u) entries[rho] = deep_entry_build(p - 1u, q, first_deep, rho);
+  else viol_by_e[row * kDeepMaxEntries + rho] = deep_viol_build(p - 1u, q, first_deep, rho, row);
 }
 
 // ----------------------------------------------------------------- doubling
@@ -793,7 +798,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         const uint32_t v = virtual_rank(in, r);
         open_v[wave][lane] = v;
         DeepTable no_table;
-        no_table.entries = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
+        no_table.entries = nullptr; no_table.viol_by_e = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
         MemoOut unused;
         viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none, false,
                                                 no_table, unused);
@@ -1260,7 +1265,8 @@ namespace {
 // kernel that reads it), or none: no workspace, or p has too few levels above the deep ones.
 // Returns false when a launch failed.
 // Workspace of the *_ws calls: [table of deep entries][count of open entries][open entries].
-constexpr size_t kTableBytes = (size_t)kDeepMaxEntries * sizeof(uint4) + 256u;
+constexpr size_t kEntriesBytes = (size_t)kDeepMaxEntries * sizeof(uint4) + 256u;
+constexpr size_t kTableBytes = kEntriesBytes + (size_t)kDeepEs * kDeepMaxEntries * sizeof(uint16_t) + 256u;
 uint32_t open_list_capacity(uint32_t p) {
   const uint64_t want = (uint64_t)p / 8u + 4096u;    // p = 1,000,003 leaves 39,000 open, p = 2^20 + 1 fewer than p / 16
   return (uint32_t)(want < (1ull << 22) ? want : (1ull << 22));
@@ -1272,7 +1278,7 @@ uint32_t open_list_capacity(uint32_t p) {
 constexpr uint64_t kTableMinRanks = 1ull << 21;
 
 bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStream_t st, DeepTable &table) {
-  table.entries = nullptr; table.first_deep = 0; table.n_rho = 0;
+  table.entries = nullptr; table.viol_by_e = nullptr; table.first_deep = 0; table.n_rho = 0;
   if (!workspace || q <= 0 || n_ranks < kTableMinRanks) return true;
   uint32_t first_deep = 0;                         // as first_deep_level() on the device
   if (p - 1u >= kLockstepSkip) {
@@ -1282,11 +1288,14 @@ bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStre
   if (first_deep < kDeepMinUpperLevels + 1u) return true;
   const uint32_t n_rho = ((p - 1u) >> (first_deep - 1u)) + 1u;      // smallest skip above the deep levels
   if (n_rho > kDeepMaxEntries) return true;
-  uint4 *entries = reinterpret_cast<uint4 *>(align_up(reinterpret_cast<uintptr_t>(workspace), 256));
-  hipLaunchKernelGGL(k_deep_table, dim3((n_rho + kBlock - 1) / kBlock), dim3(kBlock), 0, st, entries, p,
-                     (uint32_t)q, first_deep, n_rho);
+  const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256);
+  uint4 *entries = reinterpret_cast<uint4 *>(base);
+  uint16_t *viol_by_e = reinterpret_cast<uint16_t *>(base + kEntriesBytes);
+  const uint32_t blocks_per_row = (n_rho + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(k_deep_table, dim3(blocks_per_row * kDeepEs), dim3(kBlock), 0, st, entries, viol_by_e, p,
+                     (uint32_t)q, first_deep, n_rho, blocks_per_row);
   if (!launch_ok()) return false;
-  table.entries = entries; table.first_deep = first_deep; table.n_rho = n_rho;
+  table.entries = entries; table.viol_by_e = viol_by_e; table.first_deep = first_deep; table.n_rho = n_rho;
   return true;
 }
 

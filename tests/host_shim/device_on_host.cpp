@@ -139,7 +139,7 @@ int shim_schedules_ranks(uint32_t p, uint32_t root, const uint32_t *ranks, uint6
       LockstepCache none;
       lockstep_cache_init(none, nullptr);
       DeepTable no_table;
-      no_table.entries = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
+      no_table.entries = nullptr; no_table.viol_by_e = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
       MemoOut unused;
       const uint32_t viol = compute_rank_phase1<false, true>(in, v, buf, buf + q, b, fl, none, false,
                                                              no_table, unused);
@@ -175,16 +175,21 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   const Instance in = make_instance(p, q, root);
   uint64_t borrowed = 0;
   static uint4 entries[kDeepMaxEntries];
+  static uint16_t viol_by_e[kDeepEs * kDeepMaxEntries];
   DeepTable table;
-  table.entries = nullptr; table.first_deep = 0; table.n_rho = 0;
+  table.entries = nullptr; table.viol_by_e = nullptr; table.first_deep = 0; table.n_rho = 0;
   g_from_table = 0; g_generic = 0;
   if (use_table && q > 0 && first_deep_level(p - 1u) >= kDeepMinUpperLevels + 1u) {
     table.first_deep = first_deep_level(p - 1u);
     table.n_rho = deep_table_rhos(p - 1u, table.first_deep);
     if (table.n_rho > kDeepMaxEntries) return -1;
-    for (uint32_t rho = 0; rho < table.n_rho; ++rho)
+    for (uint32_t rho = 0; rho < table.n_rho; ++rho) {
       entries[rho] = deep_entry_build(p - 1u, q, table.first_deep, rho);
+      for (uint32_t less = 1; less < kDeepEs; ++less)
+        viol_by_e[less * kDeepMaxEntries + rho] = deep_viol_build(p - 1u, q, table.first_deep, rho, less);
+    }
     table.entries = entries;
+    table.viol_by_e = viol_by_e;
   }
   // one slice that is reused (rows of the previous tile stay where they are until they are
   // overwritten) and a copy of the receive rows of the tile above

@@ -296,6 +296,7 @@ __device__ __forceinline__ uint32_t first_level_taken(uint32_t pm1, uint32_t v) 
 // Number of levels at the top whose skip is at least min_skip (levels 1 .. n).
 constexpr uint32_t kTopSkip = 4096u;
 constexpr uint32_t kUpperSkip = 65536u;
+constexpr uint32_t kCutSkip = 65536u;         // where the lockstep stretch is cut in two, see ascent_run
 __device__ __forceinline__ uint32_t top_level_count(uint32_t pm1, uint32_t q, uint32_t min_skip = kTopSkip) {
   if (pm1 < min_skip) return 0u;
   // skip_at_level(j) >= min_skip  <=>  (pm1 >> j) >= min_skip - 1
@@ -328,9 +329,11 @@ __device__ __forceinline__ uint32_t wave_max32(uint32_t x) {
 // What a wavefront remembers from one tile of its run to replay on the next
 // ones: the lockstep stretch of the receive search (see recv_ascent) and the
 // state after the top levels of the pass (see compute_rank_phase1).  Everything
-// that is the same in all lanes lives in kRecordWords words of the wavefront's
-// own LDS (`mem`), so that it costs no registers between tiles; D, M and top_v
-// are this lane's own.
+// is kept in kRecordWords words of the wavefront's own LDS (`mem`), so that it costs no
+// registers between tiles.  The lanes of a tile that records hold consecutive ranks, so what is
+// a lane's own (v; D and M of the search) is the first lane's value plus the lane's number, or
+// the same in all lanes, and the first lane's value stands for all of them; a tile for which
+// that does not hold leaves no record.
 enum RecordWord : uint32_t {
   kRecLevels = 0,                   // 32 bytes: level accepted for round k, k = k_entry .. q-1
   kRecValid = 8, kRecK, kRecLive, kRecPathr, kRecJ,   // state on entry to the stretch
@@ -346,31 +349,60 @@ enum RecordWord : uint32_t {
   // the uppermost of the top levels (skips of kUpperSkip and more) once more, as a record of their own
   kUpValid, kUpLevels, kUpV0,       // valid, how many, the first lane's v when they were recorded
   kUpT, kUpTw, kUpJb, kUpPathr, kUpE, kUpViol, kUpBits, kUpC, kUpMargin,
-  kRecordWords = 48
+  // the second part of the lockstep stretch (from round kMidK on) as a record of its own
+  kMidValid, kMidK, kMidLive, kMidPathr, kMidJ, kMidMargin, kMidIters, kMidRoundOfB,
+  kMidReplays,                      // tiles that took the second part alone (statistics)
+  // D and M of the recording tile's lanes on entry to the stretch and to its second part: the
+  // first lane's values; lane l had D + l and M + l (kRamp set) or M (kRamp clear)
+  kRecD0, kRecM0, kRecRamp, kMidD0, kMidM0, kMidRamp,
+  kTopV0,                           // the first lane's v when the top levels were recorded
+  kRecordWords = 64
 };
 constexpr uint32_t kNoRound = 0xFFFFFFFFu;
+constexpr uint32_t kWaveLanes = 64u;
 
-struct LockstepCache {
+// kCanSplit: the code that records the lockstep stretch in two parts is compiled in (it costs
+// registers and code also where it does not run); `split` then switches it on.
+template <bool kCanSplit>
+struct LockstepCacheT {
+  static constexpr bool can_split = kCanSplit;
   uint32_t *mem;
-  uint32_t D, M;                    // this lane's D and M on entry to the recorded stretch
-  uint32_t top_v;                   // this lane's v when the top levels were recorded
   uint32_t lane;                    // this lane's number in the wavefront
+  bool split;                       // record the lockstep stretch in two parts (pays in long runs of tiles)
 };
+using LockstepCache = LockstepCacheT<false>;
+using LockstepCacheSplit = LockstepCacheT<true>;
+
+// D and M of the lanes of a wavefront as first lane's value + lane's number (D always, M if
+// `ramp`) or the same in all lanes (M otherwise).  Returns whether they are of that form.
+__device__ __forceinline__ bool lanes_in_a_row(uint32_t D, uint32_t M, uint32_t lane, uint32_t &D0,
+                                               uint32_t &M0, uint32_t &ramp) {
+  D0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)D);
+  M0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)M);
+  const bool flat = !__any(M != M0);
+  const bool ramp_m = !__any(M - lane != M0);
+  const bool ramp_d = !__any(D - lane != D0);
+  ramp = flat ? 0u : 1u;
+  return ramp_d && (flat || ramp_m);
+}
 
 // mem: kRecordWords words of the wavefront's own, or null for a rank on its own (no records).
-__device__ __forceinline__ void lockstep_cache_init(LockstepCache &c, uint32_t *mem, uint32_t lane = 0u) {
+template <typename Cache>
+__device__ __forceinline__ void lockstep_cache_init(Cache &c, uint32_t *mem, uint32_t lane = 0u,
+                                                    bool split = false) {
   c.mem = mem;
-  c.D = 0; c.M = 0; c.top_v = 0;
   c.lane = lane;
+  c.split = split;
   if (mem != nullptr) {
     mem[kRecValid] = 0; mem[kRecReplays] = 0; mem[kTopValid] = 0; mem[kTopReplays] = 0;
-    mem[kRecRowsHeld] = 0; mem[kUpValid] = 0;
+    mem[kRecRowsHeld] = 0; mem[kUpValid] = 0; mem[kMidValid] = 0; mem[kMidReplays] = 0;
   }
 }
 
 // The wavefront's rows have been written by something other than its tiles (or are about to be):
 // nothing that relies on entries staying in them from tile to tile may be taken over.
-__device__ __forceinline__ void lockstep_cache_rows_lost(LockstepCache &c) {
+template <typename Cache>
+__device__ __forceinline__ void lockstep_cache_rows_lost(Cache &c) {
   c.mem[kTopValid] = 0; c.mem[kUpValid] = 0; c.mem[kRecRowsHeld] = 0;
 }
 
@@ -404,7 +436,20 @@ __device__ __forceinline__ void lockstep_cache_rows_lost(LockstepCache &c) {
 //    distance makes the same moves, and takes the recorded accepts (level per
 //    round) instead of running the loop.  The same bound, applied to the
 //    differences between the lanes of the recording tile, shows that its lanes
-//    did make the same moves.  `use_cache` = false: no replay; when it is true,
+//    did make the same moves.  The tests of the first rounds of the stretch, among
+//    skips of a few thousand, flip every few tiles; those of the rounds with skips of
+//    kUpperSkip and more hold for hundreds of tiles.  The stretch is therefore
+//    recorded in two parts, cut where round q - (levels with such skips) begins: a
+//    tile that cannot take the whole stretch over makes the moves of the first part
+//    and, if it arrives at the cut in the recorded state with D and M within the
+//    second part's margin, takes the second part from the record.  The whole stretch
+//    can then be taken over again from this tile's D and M on entry, with what is
+//    left of the second part's margin (its own less the shift at the cut; shifts
+//    add up, and the shift at the cut of a later tile is no more than its shift on
+//    entry, since D and M at the cut are D + c, M + c or constants too).  The second
+//    part's bookkeeping costs a recording tile some instructions; wavefronts with
+//    runs of a few tiles only record the stretch in one part (`split` of the cache).
+//    `use_cache` = false: no replay; when it is true,
 //    all lanes of the wavefront must be in the call, and every lane must pass the
 //    same row to `emit` from tile to tile: the accepts of the stretch are minus the
 //    level in every lane (only block b, for level 0, is the lane's own), so a tile
@@ -459,10 +504,10 @@ __device__ __forceinline__ uint32_t deep_level_mask(uint32_t pm1) {
 // move than the one branch a wavefront in lockstep takes, and fewer than all the branches a
 // wavefront of unrelated ranks takes one after the other: for lists of arbitrary ranks and for
 // the searches that answer violations.
-template <bool kPrefix, bool kFlat = false, typename Emit>
+template <bool kPrefix, bool kFlat = false, typename Emit, typename Cache>
 __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_t jb, uint32_t k_last,
                                                AscentState &a, uint32_t anom_in, bool &anomaly,
-                                               Emit emit, LockstepCache &cache, bool use_cache) {
+                                               Emit emit, Cache &cache, bool use_cache) {
   const int b = (int)q - (int)jb;
   uint32_t anom = anom_in;
   uint32_t D = a.D, M = a.M, sk1 = a.sk1, k = a.k, j = a.j, live = a.live, pathr = a.pathr;
@@ -478,6 +523,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
   bool go = k < k_stop && !((int)j < 0 && pathr == 0);
   uint32_t it = 0;
   uint32_t margin = 0xFFFFFFFFu;
+  uint32_t b_word = kRecRoundOfB;     // where a recorded move notes the round of level 0
   // One move of the state machine.  With kTrack, every test that decides the
   // move also lowers `margin` to its flip distance.
   auto move = [&](auto track_tag) {
@@ -520,7 +566,7 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
         emit(k, jj == 0 ? b : -(int)jj);
         if (kTrack) {
           reinterpret_cast<uint8_t *>(cache.mem)[k] = (uint8_t)jj;
-          if (jj == 0u) cache.mem[kRecRoundOfB] = k;
+          if (jj == 0u) cache.mem[b_word] = k;
         }
         live ^= 1u << jj;
         see(sk1, t + 2u);
@@ -568,29 +614,42 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
     anomaly = anomaly || anom != 0 || it >= cap;
     return k;
   }
-  // Lockstep stretch: replayed, recorded, or simply run.
+  // Lockstep stretch: replayed, recorded, or simply run.  (Whatever is the same in all lanes is
+  // read from the first lane, so that it is held in scalar registers.)
   bool replayed = false, record = false;
-  uint32_t D_in = D, M_in = M, k_in = k, live_in = live, pathr_in = pathr, j_in = j, it_in = it;
+  auto emit_recorded = [&](uint32_t from) {
+    for (uint32_t kk = from; kk < q; ++kk) {
+      const uint32_t jj = reinterpret_cast<const uint8_t *>(cache.mem)[kk];
+      emit(kk, jj == 0 ? b : -(int)jj);
+    }
+  };
+  // D - (D0 + lane), M - (M0 + lane or 0): how far this tile's lanes are from a recorded tile's
+  auto shift_from = [&](uint32_t word_d0, uint32_t &dD, uint32_t &dM) {
+    dD = D - (cache.mem[word_d0] + cache.lane);
+    dM = M - (cache.mem[word_d0 + 1u] + (cache.mem[word_d0 + 2u] != 0u ? cache.lane : 0u));
+  };
+  static_assert(kRecM0 == kRecD0 + 1 && kRecRamp == kRecD0 + 2 && kMidM0 == kMidD0 + 1 && kMidRamp == kMidD0 + 2,
+                "D0, M0 and the ramp flag of a record follow one another");
+  uint32_t it_in = 0;
   if (use_cache && k_stop == q) {
     const uint32_t k0 = lane0_of(k), l0 = lane0_of(live), p0 = lane0_of(pathr), j0 = lane0_of(j);
     const bool shared = go && k == k0 && live == l0 && pathr == p0 && j == j0;
     if (!__any(!shared)) {
       if (cache.mem[kRecValid] && k0 == cache.mem[kRecK] && l0 == cache.mem[kRecLive] && p0 == cache.mem[kRecPathr] &&
           j0 == cache.mem[kRecJ]) {
-        const uint32_t dD = D - cache.D, dM = M - cache.M;
+        uint32_t dD, dM;
+        shift_from(kRecD0, dD, dM);
         const uint32_t far = stretch_shift(dD, dM);
         const uint32_t dD0 = lane0_of(dD), dM0 = lane0_of(dM);   // read by all lanes, whatever the tests say
         const bool ok = dD == dD0 && dM == dM0 && far <= cache.mem[kRecMargin] &&
                         it + cache.mem[kRecIters] <= cap;
         if (!__any(!ok)) {
           if (cache.mem[kRecRowsHeld] != 0u) {
-            const uint32_t kb = cache.mem[kRecRoundOfB];
+            const uint32_t kb = cache.mem[kRecRoundOfB], kb2 = cache.mem[kMidRoundOfB];
             if (kb != kNoRound) emit(kb, b);
+            if (kb2 != kNoRound) emit(kb2, b);
           } else {
-            for (uint32_t kk = k0; kk < q; ++kk) {
-              const uint32_t jj = reinterpret_cast<const uint8_t *>(cache.mem)[kk];
-              emit(kk, jj == 0 ? b : -(int)jj);
-            }
+            emit_recorded(k0);
             cache.mem[kRecRowsHeld] = 1u;
           }
           k = q;
@@ -600,25 +659,101 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
           cache.mem[kRecReplays] = cache.mem[kRecReplays] + 1u;
         }
       }
-      record = !replayed;
+      if (!replayed) {
+        // A record of the whole stretch starts here; it becomes valid at the end, if all goes well.
+        record = true;
+        uint32_t D0, M0, ramp;
+        const bool in_a_row = lanes_in_a_row(D, M, cache.lane, D0, M0, ramp);
+        cache.mem[kRecValid] = 0u;
+        cache.mem[kRecK] = k0; cache.mem[kRecLive] = l0; cache.mem[kRecPathr] = p0; cache.mem[kRecJ] = j0;
+        cache.mem[kRecD0] = D0; cache.mem[kRecM0] = M0; cache.mem[kRecRamp] = ramp;
+        // lanes that are not in a row leave no record: a margin of 0 is never enough (see below)
+        cache.mem[kRecMargin] = in_a_row ? 0xFFFFFFFFu : 0u;
+        it_in = lane0_of(it);
+      }
     }
   }
   // rows written by anything but this record's own accepts no longer hold them
   if (!replayed && cache.mem != nullptr) cache.mem[kRecRowsHeld] = 0u;
-  if (record) {
-    cache.mem[kRecRoundOfB] = kNoRound;
-    for (; it < cap && go; ++it) move(TrackOn{});
-    // usable if it ran to the end without incident and no lane can have left the others
-    const uint32_t apart = stretch_shift(D_in - lane0_of(D_in), M_in - lane0_of(M_in));
-    const uint32_t m_all = wave_min32(margin);
-    const uint32_t apart_all = wave_max32(apart);
-    const bool fine = k == q && anom == 0;
-    cache.mem[kRecValid] = (uint32_t)(!__any(!fine) && apart_all <= m_all);
-    cache.mem[kRecK] = k_in; cache.mem[kRecLive] = live_in; cache.mem[kRecPathr] = pathr_in; cache.mem[kRecJ] = j_in;
-    cache.D = D_in; cache.M = M_in;
-    cache.mem[kRecMargin] = m_all;
-    cache.mem[kRecIters] = it - it_in;
-    cache.mem[kRecRowsHeld] = cache.mem[kRecValid];    // all 64 rows were written by the stretch just now
+  if (use_cache && k_stop == q && !replayed) {
+    // The moves of the first part, with their flip distances if the whole stretch can be recorded
+    // (`record`: the lanes share the state on entry); lanes that have parted earlier usually
+    // meet again at the cut.  The cut is the same in all lanes; a stretch that begins at or beyond
+    // it, or an instance without such skips, has one part only.
+    const uint32_t k_cut = q - top_level_count(pm1, q, kCutSkip);
+    const bool two_parts = Cache::can_split && cache.split && k_cut < q && !__any(go && k >= k_cut);
+    b_word = kRecRoundOfB;
+    if (record) {
+      cache.mem[kRecRoundOfB] = kNoRound;
+      if (!two_parts) { cache.mem[kMidRoundOfB] = kNoRound; cache.mem[kMidValid] = 0u; }   // its accepts are overwritten
+      for (; it < cap && go && (!two_parts || k < k_cut); ++it) move(TrackOn{});
+    } else {
+      for (; it < cap && go && (!two_parts || k < k_cut); ++it) move(TrackOff{});
+    }
+    // the smallest flip distance of the first part over all lanes (only a recording tile has one)
+    const uint32_t m_first = record ? lane0_of(wave_min32(margin)) : 0u;
+    uint32_t second_left = 0xFFFFFFFFu;        // how far the entry state may still move for the second part
+    bool second_fine = true;                   // the second part is known to hold for all lanes of this tile
+    if (two_parts) {
+      margin = 0xFFFFFFFFu;
+      const uint32_t kc = lane0_of(k), lc = lane0_of(live), pc = lane0_of(pathr), jc = lane0_of(j);
+      const bool at_cut = go && k == kc && live == lc && pathr == pc && j == jc;
+      bool taken = false;
+      if (!__any(!at_cut)) {
+        if (cache.mem[kMidValid] && kc == cache.mem[kMidK] && lc == cache.mem[kMidLive] && pc == cache.mem[kMidPathr] &&
+            jc == cache.mem[kMidJ]) {
+          uint32_t dD, dM;
+          shift_from(kMidD0, dD, dM);
+          const uint32_t far = stretch_shift(dD, dM);
+          const uint32_t dD0 = lane0_of(dD), dM0 = lane0_of(dM);
+          const bool ok = dD == dD0 && dM == dM0 && far <= cache.mem[kMidMargin] &&
+                          it + cache.mem[kMidIters] <= cap;
+          if (!__any(!ok)) {
+            emit_recorded(kc);
+            k = q;
+            it += cache.mem[kMidIters];
+            go = false;
+            taken = true;
+            second_left = cache.mem[kMidMargin] - lane0_of(far);
+            cache.mem[kMidReplays] = cache.mem[kMidReplays] + 1u;
+          }
+        }
+        if (!taken) {                            // the second part by its moves, recorded
+          uint32_t D0, M0, ramp;
+          const bool in_a_row = lanes_in_a_row(D, M, cache.lane, D0, M0, ramp);
+          const uint32_t it_cut = lane0_of(it);
+          cache.mem[kMidValid] = 0u;
+          cache.mem[kMidK] = kc; cache.mem[kMidLive] = lc; cache.mem[kMidPathr] = pc; cache.mem[kMidJ] = jc;
+          cache.mem[kMidD0] = D0; cache.mem[kMidM0] = M0; cache.mem[kMidRamp] = ramp;
+          // a record of the whole stretch made by an earlier tile ends in the accepts overwritten now
+          if (!record) cache.mem[kRecValid] = 0u;
+          b_word = kMidRoundOfB;
+          cache.mem[kMidRoundOfB] = kNoRound;
+          for (; it < cap && go; ++it) move(TrackOn{});
+          const uint32_t m_all = lane0_of(wave_min32(margin));
+          const bool fine = k == q && anom == 0;
+          // lanes in a row are at most 63 apart in D and M: stretch_shift(63, 0 or 63) = 64
+          second_fine = in_a_row && !__any(!fine) && (uint32_t)kWaveLanes <= m_all;
+          cache.mem[kMidValid] = (uint32_t)second_fine;
+          cache.mem[kMidMargin] = m_all;
+          cache.mem[kMidIters] = lane0_of(it) - it_cut;
+          second_left = m_all;
+        }
+      } else {                                   // the lanes are not together at the cut: to the end as they are
+        for (; it < cap && go; ++it) move(TrackOff{});
+        second_fine = false;
+      }
+    }
+    if (record) {
+      // usable as a whole if it ran to the end without incident and no lane can have left the others
+      const uint32_t m_both = m_first < second_left ? m_first : second_left;
+      const uint32_t m_all = cache.mem[kRecMargin] < m_both ? cache.mem[kRecMargin] : m_both;   // 0: not in a row
+      const bool fine = k == q && anom == 0;
+      cache.mem[kRecValid] = (uint32_t)(second_fine && !__any(!fine) && (uint32_t)kWaveLanes <= m_all);
+      cache.mem[kRecMargin] = m_all;
+      cache.mem[kRecIters] = lane0_of(it) - it_in;
+      cache.mem[kRecRowsHeld] = cache.mem[kRecValid];    // all 64 rows hold the accepts of both parts now
+    }
   } else {
     for (; it < cap && go; ++it) move(TrackOff{});
   }
@@ -626,12 +761,12 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
   return k;
 }
 
-template <bool kFlat = false, typename Emit>
+template <bool kFlat = false, typename Emit, typename Cache>
 __device__ __forceinline__ uint32_t recv_ascent(uint32_t p, uint32_t pm1, uint32_t q,
                                                 uint32_t jb, uint32_t k_last, int W,
                                                 uint32_t pathr, uint32_t anom_in,
                                                 bool &anomaly, Emit emit,
-                                                LockstepCache &cache, bool use_cache) {
+                                                Cache &cache, bool use_cache) {
   (void)p;
   AscentState a = ascent_start(pm1, q, jb, W, pathr, emit);
   return ascent_run<false, kFlat>(pm1, q, jb, k_last, a, anom_in, anomaly, emit, cache, use_cache);
@@ -758,11 +893,11 @@ struct MemoOut {
   uint32_t rho, room;
 };
 
-template <bool kMemo, bool kFlat = false>
+template <bool kMemo, bool kFlat = false, typename Cache>
 __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
                                                         int8_t *recv_row, int8_t *send_row,
                                                         int &b_out, uint32_t &flags,
-                                                        LockstepCache &cache, bool use_cache,
+                                                        Cache &cache, bool use_cache,
                                                         const DeepTable &table, MemoOut &memo) {
   const uint32_t q = in.q;
   flags = 0;
@@ -786,10 +921,11 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
   uint32_t margin_own = 0xFFFFFFFFu;         // kMemo: flip distance of this lane's own tests
   bool took_over = false;
   if (n_top >= 4u) {
-    const uint32_t dv = v - cache.top_v;
-    const uint32_t dv0 = lane0_of(dv);
-    const uint32_t away = abs_difference(v, cache.top_v);
-    const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && dv == dv0 &&
+    // the lanes of a tile that uses the records hold consecutive v: the first lane's stands for all
+    const uint32_t v0 = lane0_of(v);
+    const bool in_a_row = v - cache.lane == v0;
+    const uint32_t away = abs_difference(v0, cache.mem[kTopV0]);
+    const bool near = cache.mem[kTopValid] != 0u && cache.mem[kTopLevels] == n_top && in_a_row &&
                       away + 1u <= cache.mem[kTopMargin];
     if (!__any(!near)) {
       s.rem = v - cache.mem[kTopT];
@@ -810,8 +946,6 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       // of such a tile hold consecutive v, so the first lane's v stands for all of them.
       const uint32_t n_up = top_level_count(in.pm1, q, kUpperSkip);
       if (n_up >= 4u && n_up < n_top) {
-        const uint32_t v0 = lane0_of(v);
-        const bool in_a_row = v - cache.lane == v0;
         const uint32_t away_up = abs_difference(v0, cache.mem[kUpV0]);
         const bool near_up = cache.mem[kUpValid] != 0u && cache.mem[kUpLevels] == n_up && in_a_row &&
                              away_up + 1u <= cache.mem[kUpMargin];
@@ -850,11 +984,11 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
       const uint32_t T0 = lane0_of(T), Tw0 = lane0_of(Tw), jb0 = lane0_of(s.jb), pathr0 = lane0_of(s.pathr),
                      e0 = lane0_of(s.e), c0 = lane0_of((uint32_t)s.c), viol0 = lane0_of(s.viol),
                      bits0 = lane0_of(bits);
-      const bool same = T == T0 && Tw == Tw0 && s.jb == jb0 && s.pathr == pathr0 && s.e == e0 &&
+      const bool same = in_a_row && T == T0 && Tw == Tw0 && s.jb == jb0 && s.pathr == pathr0 && s.e == e0 &&
                         (uint32_t)s.c == c0 && s.viol == viol0 && bits == bits0;
       cache.mem[kTopValid] = (uint32_t)!__any(!same);
       cache.mem[kTopLevels] = n_top;
-      cache.top_v = v;
+      cache.mem[kTopV0] = v0;
       cache.mem[kTopT] = T0; cache.mem[kTopTw] = Tw0; cache.mem[kTopJb] = jb0;
       cache.mem[kTopPathr] = pathr0; cache.mem[kTopE] = e0;
       cache.mem[kTopC] = c0; cache.mem[kTopViol] = viol0;
@@ -949,10 +1083,11 @@ __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint
 }
 
 // Without the table of deep entries.
+template <typename Cache>
 __device__ __forceinline__ uint32_t compute_rank_phase1(const Instance &in, uint32_t v,
                                                         int8_t *recv_row, int8_t *send_row,
                                                         int &b_out, uint32_t &flags,
-                                                        LockstepCache &cache, bool use_cache) {
+                                                        Cache &cache, bool use_cache) {
   DeepTable none;
   none.entries = nullptr; none.viol_by_e = nullptr; none.first_deep = 0; none.n_rho = 0;
   MemoOut unused;

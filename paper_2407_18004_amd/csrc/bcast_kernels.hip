@@ -91,6 +91,11 @@ __device__ __forceinline__ void tile_out(const uint32_t *lds_words, int32_t *dst
 // tiles.  The workgroups form kRunClasses classes by their number (class_blocks consecutive
 // workgroups each); a class owns a contiguous range of tiles and deals it out evenly, so classes
 // can be given runs of different lengths.
+// k_digest records the lockstep stretch in two parts in runs of this many tiles and more (4 % faster
+// with runs of 43 tiles).  k_schedules does not, and is compiled without that code: its long launches
+// are bound by their stores, its short ones by latency, and the code alone cost the table of
+// p = 1,000,003 3 us.
+constexpr uint64_t kSplitRunTiles = 8;
 constexpr uint32_t kRunClasses = 8;
 struct RunSplit {
   uint32_t class_blocks;            // workgroups per class
@@ -156,12 +161,12 @@ struct TileState {
 // violations of Algorithm 6 resolved from rows of the same tile or else by
 // search on the spot: for p = 2^q and 2^q - 1, which have next to none.
 // slices: the workgroup's four slices, slice_w words each.
-template <bool kMemo>
+template <bool kMemo, typename Cache>
 __device__ __forceinline__ TileState tile_rows(const Instance &in, uint64_t r_begin,
                                                uint64_t n_ranks, uint64_t tile, uint64_t n_tiles,
                                                uint32_t *slices, uint32_t slice_w, uint32_t pitch,
                                                uint32_t send_off, uint32_t lane, uint32_t wave,
-                                               LockstepCache &cache, bool use_cache,
+                                               Cache &cache, bool use_cache,
                                                const DeepTable &table) {
   TileState st;
   st.v = 0; st.flags = 0; st.b = 0;
@@ -292,8 +297,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   tile_run(prm.runs, t_lo, t_hi);
   LockstepCache record;
   const bool long_run = t_hi - t_lo >= 3u;     // recording costs more than it saves on two tiles
+  const bool split_stretch = false;            // tables are bound by their stores or by latency: see kSplitRunTiles
   if (!kShare) {
-    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane);
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane, split_stretch);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
                                             pitch, send_off, lane, wave, record, long_run, prm.table);
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
   int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
   uint32_t *queue = words + slice_w + 16u * q;
-  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane);
+  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane, split_stretch);
   const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
@@ -518,10 +524,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   };
   uint64_t t_lo, t_hi;
   tile_run(prm.runs, t_lo, t_hi);
-  LockstepCache record;
+  LockstepCacheSplit record;
   const bool long_run = t_hi - t_lo >= 3u;
+  const bool split_stretch = t_hi - t_lo >= kSplitRunTiles;
   if (!kShare) {
-    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane);
+    lockstep_cache_init(record, lds_dyn + kWavesPerBlock * slice_w + wave * kRecordWords, lane, split_stretch);
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
                                             pitch, q, lane, wave, record, long_run, prm.table);
@@ -532,7 +539,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   } else {
     int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
     uint32_t *queue = words + slice_w + 16u * q;
-    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane);
+    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane, split_stretch);
     const uint64_t run_row0 = t_lo * kWave;
     uint32_t n_queued = 0;                     // the same in all lanes; at most 63 between tiles
     uint32_t n_valid_above = 0;

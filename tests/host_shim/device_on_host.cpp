@@ -112,7 +112,7 @@ static uint32_t q_of(uint32_t p) {
   return q;
 }
 
-static uint64_t g_replays = 0, g_top_replays = 0, g_from_table = 0, g_generic = 0;
+static uint64_t g_replays = 0, g_top_replays = 0, g_mid_replays = 0, g_from_table = 0, g_generic = 0;
 
 extern "C" {
 
@@ -120,6 +120,8 @@ extern "C" {
 uint64_t shim_last_replays(void) { return g_replays; }
 // ... and that took over the state after the top levels
 uint64_t shim_last_top_replays(void) { return g_top_replays; }
+// tiles that took only the second part of the lockstep stretch from the record
+uint64_t shim_last_mid_replays(void) { return g_mid_replays; }
 
 // rows: m rows of 2q int32 (recv then send) for the physical ranks given.
 // flags_out/hash_out (may be NULL): per-rank flags and row hash.
@@ -196,10 +198,11 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   alignas(4) static int8_t tile[64 * 68];      // rows digest_row_pitch(q) apart, as k_digest keeps them
   const uint32_t pitch = digest_row_pitch(q);
   static int8_t above[64 * 31];
-  static LockstepCache caches[64];            // D, M, top_v are per lane ...
+  static LockstepCacheSplit caches[64];            // one per lane (its number) ...
   static uint32_t record_mem[kRecordWords];   // ... the rest is the wavefront's
   g_replays = 0;
   g_top_replays = 0;
+  g_mid_replays = 0;
   shim_wave::mismatches = 0;
   shim_wave::operations = 0;
   const uint64_t n_tiles = (n + 63) / 64;
@@ -207,7 +210,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
   for (uint64_t run0 = 0; run0 < n_tiles; run0 += per_run) {
     const uint64_t run1 = run0 + per_run < n_tiles ? run0 + per_run : n_tiles;
     memset(tile, 0x55, sizeof tile);
-    for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem, (uint32_t)l);
+    for (int l = 0; l < 64; ++l) lockstep_cache_init(caches[l], record_mem, (uint32_t)l, run1 - run0 >= 8);
     const bool long_run = run1 - run0 >= 3;   // as in the kernels
     uint32_t n_valid_next = 0;
     const int8_t *next_recv = nullptr;
@@ -260,6 +263,7 @@ int shim_schedules_tiles(uint32_t p, uint32_t root, uint32_t r_begin, uint64_t n
     // GPU: 64 per tile that replayed
     g_replays += record_mem[kRecReplays] / 64u;
     g_top_replays += record_mem[kTopReplays] / 64u;
+    g_mid_replays += record_mem[kMidReplays] / 64u;
   }
   if (n_from_tile) *n_from_tile = borrowed;
   return (int)q;

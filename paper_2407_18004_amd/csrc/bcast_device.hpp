@@ -317,14 +317,6 @@ __device__ __forceinline__ uint32_t wave_min32(uint32_t x) {
   }
   return x;
 }
-__device__ __forceinline__ uint32_t wave_max32(uint32_t x) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    const uint32_t y = (uint32_t)__shfl_xor((int)x, m, 64);
-    x = y > x ? y : x;
-  }
-  return x;
-}
 
 // What a wavefront remembers from one tile of its run to replay on the next
 // ones: the lockstep stretch of the receive search (see recv_ascent) and the

@@ -778,6 +778,25 @@ def test_digest_and_edge_check_for_every_number_of_rounds(q):
             assert xs == oracle.edgecheck(p, root, a, a + n, send_mode=1), (p, "edges, workspace")
 
 
+@pytest.mark.parametrize("q", list(range(25, 32)))
+def test_long_runs_for_every_large_number_of_rounds(q):
+    """Launches long enough for every wavefront to work through a dozen tiles, so that the records a
+    wavefront carries from tile to tile (top levels, lockstep stretch in two parts) and the tables in
+    the workspace are all in use, for each q that has that many ranks: digest, flags and edge check
+    against the oracle, p = 2^q - 1 and an odd p with violations, the root inside the range."""
+    n = 2**24 + 2**22 + 12345
+    odd = (1 << (q - 1)) + 1 + 2 * ((q * 2654435761) % (1 << (q - 3)))
+    for p in (2**q - 1, odd):
+        assert lib.bcast_q(p) == q and p > n
+        root = (p * 3) // 5
+        a = max(0, min(root - n // 2, p - n))
+        ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+        dg, xs = ws_digest_and_edges(p, root, a, a + n, ws)
+        assert dg == oracle.digest(p, root, a, a + n, send_mode=1), (p, "digest")
+        assert xs == oracle.edgecheck(p, root, a, a + n, send_mode=1), (p, "edges")
+        assert gpu_digest(p, root, a, a + n) == dg, (p, "digest without a workspace")
+
+
 def test_calls_with_workspace_on_the_streamed_instance():
     p = workloads.STREAMED_P
     gold = streamed_golden()

@@ -574,8 +574,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       wave_lds_sync();
       uint32_t open = 0;
       if (lane < n_here) {
-        if (batch) {                           // no neighbours here: every violation by search
-          acc_flags |= resolve_by_search(in, v, viol, send_row);
+        if (batch) {                           // no neighbours here: from the table, else by search
+          const uint32_t left = kMemo ? resolve_from_table(in, prm.table, v, memo, viol, send_row) : viol;
+          acc_flags |= resolve_by_search(in, v, left, send_row);
         } else {
           open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                     pitch, q, lane, n_here, n_valid_above);

@@ -1214,28 +1214,24 @@ RunSplit split_runs(uint64_t n_tiles, int grid) {
 }
 
 // Grid of k_schedules<true>, whose wavefronts each take one contiguous run of
-// tiles.  Long runs make the deferred violations cheap; many more workgroups
+// tiles.  Long runs make the deferred violations and the records cheap; more workgroups
 // than fit at once even out the load, because a SIMD serves its oldest
 // wavefront first and the young ones of a resident set fall behind by a factor
-// of two.  Measured on MI355X: about six tiles per wavefront is best for long
-// tables, two to four when that would leave fewer than two resident sets.  (With at most 2^25
+// of two.  Measured on MI355X: everything at once when it fits; else two tiles per wavefront
+// until that makes three resident sets, and three sets from there on (tables of 3 to 6 million
+// ranks 2-3 % faster than with two sets, the others level).  (With at most 2^25
 // tiles on 24,576 wavefronts and run lengths that differ by a factor of 1.5 from the mean, a run
 // stays below 2,100 tiles, so a row within a run fits 27 bits with room to spare: the queue
 // entries of the kernels rely on that.)
-constexpr uint64_t kRunTiles = 6;
 int run_grid(uint64_t n_tiles, uint32_t resident_per_cu) {
-  const int cap = run_grid_cap();
+  const int cap = run_grid_cap();                                 // three resident sets
   if (cap < 0) return -1;
   const uint64_t one_set = (uint64_t)cap / kRunGridPerCu * resident_per_cu;   // workgroups that fit at once
   const uint64_t per_wg = kWavesPerBlock;
   const uint64_t g_one = (n_tiles + per_wg - 1) / per_wg;        // one tile per wavefront
   if (g_one <= one_set) return (int)(g_one == 0 ? 1 : g_one);
   const uint64_t g_two = (n_tiles + per_wg * 2u - 1) / (per_wg * 2u);
-  const uint64_t floor_g = g_two < 2u * one_set ? g_two : 2u * one_set;
-  uint64_t g = (n_tiles + per_wg * kRunTiles - 1) / (per_wg * kRunTiles);
-  if (g < floor_g) g = floor_g;
-  if (g > (uint64_t)cap) g = (uint64_t)cap;
-  return (int)g;
+  return (int)(g_two < (uint64_t)cap ? g_two : (uint64_t)cap);
 }
 
 // Algorithm 6 has (next to) no violations when every skip below p is a power of

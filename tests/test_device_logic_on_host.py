@@ -47,6 +47,7 @@ def shim():
                                        ctypes.c_void_p, ctypes.c_void_p]
     lib.shim_recv_two_ways.restype = ctypes.c_uint32
     lib.shim_last_top_replays.restype = ctypes.c_uint64
+    lib.shim_last_mid_replays.restype = ctypes.c_uint64
     return lib
 
 
@@ -179,7 +180,8 @@ def test_replayed_lockstep_stretch_equals_the_search(shim):
     # over see what they see on the GPU.  Whatever is replayed must equal Algorithm 5, everywhere
     # a record can be taken over: long stretches of consecutive ranks at both ends and in the
     # middle of several p, from the top down (kernels for p with violations) and from the bottom
-    # up (kernels for p = 2^q and 2^q - 1), in one run and in runs as short as the kernels'.
+    # up (kernels for p = 2^q and 2^q - 1), in one run (long enough for the stretch to be recorded
+    # in two parts) and in runs as short as the kernels'.
     replays = 0
     cases = [(2**31 - 1, 0, 2**30 - 30000, 60000), (2**31 - 1, 12345, 2**31 - 1 - 50000, 50000),
              (2**31 - 1, 0, 0, 40000), (1000003, 0, 0, 120000), (1000003, 999999, 880000, 120003),
@@ -199,6 +201,8 @@ def test_replayed_lockstep_stretch_equals_the_search(shim):
             if p > 10**6 and run_tiles == 0:
                 assert replays_here > n // 64 // 4, (p, replays_here)     # the record is actually used
                 assert top_here > n // 64 // 4, (p, top_here)
+                if p > 2**26:     # long runs record the stretch in two parts: the second is taken alone too
+                    assert int(shim.shim_last_mid_replays()) > n // 64 // 50, (p, descending)
     assert replays > 10000
 
 

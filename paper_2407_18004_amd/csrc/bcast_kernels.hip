@@ -1276,10 +1276,11 @@ uint32_t open_list_capacity(uint32_t p) {
   return (uint32_t)(want < (1ull << 22) ? want : (1ull << 22));
 }
 
-// Building the table takes one small kernel ahead of the main one, some 15 us from launch to end;
-// it pays from a few million ranks on (measured on MI355X: tables of 2^23 ranks 1.4 times
-// faster, p = 1,000,003 10 % slower), so shorter ranges are computed without it.
-constexpr uint64_t kTableMinRanks = 1ull << 21;
+// Building the tables takes one small kernel ahead of the main one, some 12 us from launch to end;
+// it pays from a million ranks on (measured on MI355X, tables with a workspace: p = 1,000,003
+// 89 us with it against 87 without, p = 1,100,003 94 against 99, p = 2,000,003 128 against 140,
+// tables of 2^23 ranks 1.4 times faster), so shorter ranges are computed without them.
+constexpr uint64_t kTableMinRanks = 1ull << 20;
 
 bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStream_t st, DeepTable &table) {
   table.entries = nullptr; table.viol_by_e = nullptr; table.first_deep = 0; table.n_rho = 0;

@@ -617,9 +617,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
 // One lane per rho for the entries (the first blocks_per_row workgroups), then one lane per
 // (S - e, rho) for the second table (see DeepTable in the device header).
+// `counter` (or null): a word to clear for the kernel that follows (the count of open entries), which
+// saves that kernel a launch of its own.
 __global__ __launch_bounds__(kBlock) void k_deep_table(uint4 *entries, uint16_t *viol_by_e, uint32_t p,
                                                        uint32_t q, uint32_t first_deep, uint32_t n_rho,
-                                                       uint32_t blocks_per_row) {
+                                                       uint32_t blocks_per_row, uint32_t *counter) {
+  if (counter != nullptr && blockIdx.x == 0 && threadIdx.x == 0) *counter = 0;
   const uint32_t row = blockIdx.x / blocks_per_row;            // 0: entries; 1 .. kDeepEs - 1: S - e
   const uint32_t rho = (blockIdx.x - row * blocks_per_row) * kBlock + threadIdx.x;
   if (rho >= n_rho) return;
@@ -1282,7 +1285,10 @@ uint32_t open_list_capacity(uint32_t p) {
 // tables of 2^23 ranks 1.4 times faster), so shorter ranges are computed without them.
 constexpr uint64_t kTableMinRanks = 1ull << 20;
 
-bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStream_t st, DeepTable &table) {
+// `counter`: cleared by the same kernel if the table is built (see k_deep_table); *cleared says whether.
+bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStream_t st, DeepTable &table,
+                   uint32_t *counter = nullptr, bool *cleared = nullptr) {
+  if (cleared) *cleared = false;
   table.entries = nullptr; table.viol_by_e = nullptr; table.first_deep = 0; table.n_rho = 0;
   if (!workspace || q <= 0 || n_ranks < kTableMinRanks) return true;
   uint32_t first_deep = 0;                         // as first_deep_level() on the device
@@ -1298,8 +1304,9 @@ bool prepare_table(uint32_t p, int q, uint64_t n_ranks, void *workspace, hipStre
   uint16_t *viol_by_e = reinterpret_cast<uint16_t *>(base + kEntriesBytes);
   const uint32_t blocks_per_row = (n_rho + kBlock - 1) / kBlock;
   hipLaunchKernelGGL(k_deep_table, dim3(blocks_per_row * kDeepEs), dim3(kBlock), 0, st, entries, viol_by_e, p,
-                     (uint32_t)q, first_deep, n_rho, blocks_per_row);
+                     (uint32_t)q, first_deep, n_rho, blocks_per_row, counter);
   if (!launch_ok()) return false;
+  if (cleared) *cleared = counter != nullptr;
   table.entries = entries; table.viol_by_e = viol_by_e; table.first_deep = first_deep; table.n_rho = n_rho;
   return true;
 }
@@ -1334,16 +1341,20 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
   const int grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : lone_grid(blocks);
   if (grid < 0) return BCAST_EHIP;
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-  if (!prepare_table(p, q, n, workspace, (hipStream_t)stream, prm.table)) return BCAST_EHIP;
-  const bool memo = prm.table.entries != nullptr;
-  const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
-                           : (size_t)lone_block_words(prm.q) * 4u;
   prm.open_list = nullptr; prm.open_count = nullptr; prm.open_cap = 0;
   if (share && workspace) {                          // entries left open go to a list, see k_fill_open
     const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256) + kTableBytes;
     prm.open_count = reinterpret_cast<uint32_t *>(base);
     prm.open_list = reinterpret_cast<unsigned long long *>(base + 256u);
     prm.open_cap = open_list_capacity(p);
+  }
+  bool count_cleared = false;
+  if (!prepare_table(p, q, n, workspace, (hipStream_t)stream, prm.table, prm.open_count, &count_cleared))
+    return BCAST_EHIP;
+  const bool memo = prm.table.entries != nullptr;
+  const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
+                           : (size_t)lone_block_words(prm.q) * 4u;
+  if (prm.open_count != nullptr && !count_cleared) {
     hipLaunchKernelGGL(k_u32_zero, dim3(1), dim3(64), 0, (hipStream_t)stream, prm.open_count);
     if (!launch_ok()) return BCAST_EHIP;
   }

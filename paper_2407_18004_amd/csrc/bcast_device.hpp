@@ -494,8 +494,8 @@ __device__ __forceinline__ uint32_t deep_level_mask(uint32_t pm1) {
 // pending calls is complete as far as it goes and raises nothing.
 // kFlat: every move runs through one body without branches.  That costs more instructions per
 // move than the one branch a wavefront in lockstep takes, and fewer than all the branches a
-// wavefront of unrelated ranks takes one after the other: for lists of arbitrary ranks and for
-// the searches that answer violations.
+// wavefront of unrelated ranks takes one after the other: for lists of arbitrary ranks, for
+// the searches that answer violations and for the builder of the table of deep entries.
 template <bool kPrefix, bool kFlat = false, typename Emit, typename Cache>
 __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_t jb, uint32_t k_last,
                                                AscentState &a, uint32_t anom_in, bool &anomaly,
@@ -593,9 +593,8 @@ __device__ __forceinline__ uint32_t ascent_run(uint32_t pm1, uint32_t q, uint32_
     j = (post && !accept) ? kEndLevel : next_level(live, jj);
     go = k < k_stop && !((int)j < 0 && pathr == 0);
   };
-  static_assert(!(kFlat && kPrefix), "the first stretch alone is not run flat");
   if (kFlat) {
-    for (; it < cap && go; ++it) move_flat();
+    for (; it < cap && go && (!kPrefix || (live & deep) != 0u); ++it) move_flat();
     if (kPrefix) { a.D = D; a.M = M; a.sk1 = sk1; a.k = k; a.j = j; a.live = live; a.pathr = pathr; }
     anomaly = anomaly || anom != 0 || (!kPrefix && k < k_stop) || it >= cap;
     return k;
@@ -841,7 +840,8 @@ __device__ __forceinline__ uint4 deep_entry_build(uint32_t pm1, uint32_t q, uint
   bool anomaly = false;
   LockstepCache none;
   lockstep_cache_init(none, nullptr);
-  ascent_run<true>(pm1, q, s.jb, q - 1u, a, s.anom, anomaly, note, none, false);
+  // (the lanes of the builder hold unrelated rho: one branch-free body serves them best)
+  ascent_run<true, true>(pm1, q, s.jb, q - 1u, a, s.anom, anomaly, note, none, false);
   const uint32_t live_deep = a.live >> first_deep;
   const bool ok = !anomaly && all_deep && s.rem == 0u && s.jb >= first_deep && s.jb - first_deep < 16u &&
                   a.pathr == 0u && (int)a.j < 0 && a.k == n_out && a.k <= 11u && a.k < q &&

@@ -473,14 +473,22 @@ struct DigestParams {
   uint64_t *digest;
   uint32_t *flags;
   DeepTable table;                  // kernels with kMemo only
+  // Ranks that k_digest<true, ...> leaves to k_digest_listed (row of the launch), or null: then the
+  // kernel computes them again itself, 64 at a time.  rank_count: entries claimed so far (may run
+  // past rank_cap).
+  uint32_t *rank_list;
+  uint32_t *rank_count;
+  uint32_t rank_cap;
 };
+constexpr uint32_t kNoRank = 0xFFFFFFFFu;            // a slot of the list that no claim that fit covers
 
-__global__ void k_digest_init(uint64_t *digest, uint32_t *flags) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; }
+// (`count`, or null: the count of the list of ranks, cleared for the kernels that follow)
+__global__ void k_digest_init(uint64_t *digest, uint32_t *flags, uint32_t *count) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; if (count) *count = 0; }
 }
 
-__global__ void k_edges_init(uint64_t *xors) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) { xors[0] = 0; xors[1] = 0; }
+__global__ void k_edges_init(uint64_t *xors, uint32_t *count) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { xors[0] = 0; xors[1] = 0; if (count) *count = 0; }
 }
 
 // kEdges = false: digest and flags.  kEdges = true: the two XOR sums of the
@@ -551,6 +559,23 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
     // (64 of them, or what is left once the tiles are done), one rank per lane in both cases.
     for (;;) {
       const bool batch = n_queued >= (uint32_t)kWave || (tile == t_lo && n_queued != 0u);
+      if (batch && prm.rank_list != nullptr) {
+        // With a list at hand the ranks that are waiting go there (one atomic for up to 64 of them)
+        // and a second kernel computes them, which it does several times faster than a pass of
+        // this loop: there every wavefront works on such ranks and nothing else.
+        const uint32_t n_out = n_queued < (uint32_t)kWave ? n_queued : (uint32_t)kWave;
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(prm.rank_count, n_out);
+        base = lane0_of(base);
+        if (base < prm.rank_cap && n_out <= prm.rank_cap - base) {
+          if (lane < n_out) prm.rank_list[base + lane] = (uint32_t)(run_row0 + queue[n_queued - n_out + lane]);
+          n_queued -= n_out;
+          wave_lds_sync();                     // the queue is written again below
+          continue;
+        }
+        // the list is full: what this claim still covers is marked unused, the ranks stay here
+        if (base < prm.rank_cap && base + lane < prm.rank_cap) prm.rank_list[base + lane] = kNoRank;
+      }
       if (!batch && tile == t_lo) break;
       uint64_t row = 0;                        // the lane's rank, as a row of the launch
       uint32_t n_here;                         // lanes with a rank in this pass
@@ -610,6 +635,66 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
   if (kEdges) acc2 = wave_xor64(acc2);
   acc_flags = wave_or32(acc_flags);
   if (lane == 0) {
+    atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
+    if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
+    else if (acc_flags) atomicOr(prm.flags, acc_flags);
+  }
+}
+
+// The ranks that k_digest<true, ...> put on the list: each lane computes one of them on its own
+// (no neighbours, no records: the branch-free search throughout, as for lists of arbitrary
+// ranks), violations by search, and adds its hash, or its edges, to the launch's result.  (Taking
+// the deep levels and the violations from the table of deep entries here as well, the latter
+// through the to-processor's own rho, was measured and is not faster: the lanes of this kernel
+// are a third busy whichever way, and it takes a tenth of the call.)
+template <bool kEdges>
+__global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
+  extern __shared__ __align__(16) uint32_t lds_dyn[];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const Instance in = make_instance(prm.p, prm.q, prm.root);
+  const uint32_t q = prm.q;
+  const uint32_t pitch = digest_row_pitch(q);
+  int8_t *recv_row = reinterpret_cast<int8_t *>(lds_dyn + wave * digest_slice_words(q)) + lane * pitch;
+  int8_t *send_row = recv_row + q;
+  // every claim that fit was written in full; the one claim that reached past the end of the
+  // list marked its slots unused; later claims start beyond the end
+  const uint32_t claimed = *prm.rank_count;
+  const uint32_t n = claimed < prm.rank_cap ? claimed : prm.rank_cap;
+  uint64_t acc = 0, acc2 = 0;
+  uint32_t acc_flags = 0;
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  for (uint32_t i0 = (blockIdx.x * kWavesPerBlock + wave) * kWave; i0 < n; i0 += n_waves * kWave) {
+    const uint32_t row = i0 + lane < n ? prm.rank_list[i0 + lane] : kNoRank;
+    if (row != kNoRank) {
+      const uint32_t r = (uint32_t)(prm.r_begin + row);
+      const uint32_t v = virtual_rank(in, r);
+      LockstepCache none;
+      lockstep_cache_init(none, nullptr);
+      DeepTable no_table;
+      no_table.entries = nullptr; no_table.viol_by_e = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
+      MemoOut unused;
+      int b = 0;
+      uint32_t flags = 0;
+      const uint32_t viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none, false,
+                                                             no_table, unused);
+      flags |= resolve_by_search<true>(in, v, viol, send_row);
+      acc_flags |= flags;
+      if (kEdges) {
+        edge_rank(in, r, recv_row, acc, acc2);
+      } else {
+        uint64_t h;
+        uint32_t fl2;
+        digest_rank(in, r, v, b, recv_row, h, fl2);
+        acc ^= h;
+        acc_flags |= fl2;
+      }
+    }
+  }
+  acc = wave_xor64(acc);
+  if (kEdges) acc2 = wave_xor64(acc2);
+  acc_flags = wave_or32(acc_flags);
+  if (lane == 0 && (acc != 0 || acc2 != 0 || acc_flags != 0)) {
     atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
     if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
     else if (acc_flags) atomicOr(prm.flags, acc_flags);
@@ -1395,14 +1480,24 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
     return BCAST_EHIP;
   }
   hipStream_t st = (hipStream_t)stream;
-  if (edges) hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, st, out64);
-  else hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, st, out64, flags);
+  // with a workspace, the ranks that the kernel for p with violations cannot finish go to a list
+  // there (the room of the list of open entries, as 32-bit rows) and k_digest_listed computes them
+  uint32_t *rank_count = nullptr, *rank_list = nullptr;
+  if (work && share && workspace) {
+    const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256) + kTableBytes;
+    rank_count = reinterpret_cast<uint32_t *>(base);
+    rank_list = reinterpret_cast<uint32_t *>(base + 256u);
+  }
+  if (edges) hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, st, out64, rank_count);
+  else hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, st, out64, flags, rank_count);
   if (!launch_ok()) return BCAST_EHIP;
   if (!work) return BCAST_OK;
   DigestParams prm;
   prm.p = p; prm.q = (uint32_t)q; prm.root = root;
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = out64; prm.flags = edges ? nullptr : flags;
+  prm.rank_list = rank_list; prm.rank_count = rank_count;
+  prm.rank_cap = rank_list ? open_list_capacity(p) * 2u : 0u;
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
   if (!prepare_table(p, q, n, workspace, st, prm.table)) return BCAST_EHIP;
   const bool memo = prm.table.entries != nullptr;
@@ -1418,6 +1513,15 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
     else { if (memo) BCAST_LAUNCH_DIGEST(false, false, true); else BCAST_LAUNCH_DIGEST(false, false, false); }
   }
 #undef BCAST_LAUNCH_DIGEST
+  if (rank_list) {
+    if (!launch_ok()) return BCAST_EHIP;
+    const size_t lds_listed = (size_t)kWavesPerBlock * digest_slice_words(prm.q) * 4u;
+    const uint64_t most = n < prm.rank_cap ? n : prm.rank_cap;
+    const uint64_t blocks_listed = (most + kBlock - 1) / kBlock;
+    const dim3 gl((unsigned)(blocks_listed < 4096u ? blocks_listed : 4096u));
+    if (edges) hipLaunchKernelGGL((k_digest_listed<true>), gl, b, lds_listed, st, prm);
+    else hipLaunchKernelGGL((k_digest_listed<false>), gl, b, lds_listed, st, prm);
+  }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }
 

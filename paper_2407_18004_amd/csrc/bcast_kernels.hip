@@ -647,7 +647,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
 // the deep levels and the violations from the table of deep entries here as well, the latter
 // through the to-processor's own rho, was measured and is not faster: the lanes of this kernel
 // are a third busy whichever way, and it takes a tenth of the call.)
-template <bool kEdges>
 __global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -661,7 +660,7 @@ __global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
   // list marked its slots unused; later claims start beyond the end
   const uint32_t claimed = *prm.rank_count;
   const uint32_t n = claimed < prm.rank_cap ? claimed : prm.rank_cap;
-  uint64_t acc = 0, acc2 = 0;
+  uint64_t acc = 0;
   uint32_t acc_flags = 0;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   for (uint32_t i0 = (blockIdx.x * kWavesPerBlock + wave) * kWave; i0 < n; i0 += n_waves * kWave) {
@@ -680,24 +679,18 @@ __global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
                                                              no_table, unused);
       flags |= resolve_by_search<true>(in, v, viol, send_row);
       acc_flags |= flags;
-      if (kEdges) {
-        edge_rank(in, r, recv_row, acc, acc2);
-      } else {
-        uint64_t h;
-        uint32_t fl2;
-        digest_rank(in, r, v, b, recv_row, h, fl2);
-        acc ^= h;
-        acc_flags |= fl2;
-      }
+      uint64_t h;
+      uint32_t fl2;
+      digest_rank(in, r, v, b, recv_row, h, fl2);
+      acc ^= h;
+      acc_flags |= fl2;
     }
   }
   acc = wave_xor64(acc);
-  if (kEdges) acc2 = wave_xor64(acc2);
   acc_flags = wave_or32(acc_flags);
-  if (lane == 0 && (acc != 0 || acc2 != 0 || acc_flags != 0)) {
+  if (lane == 0 && (acc != 0 || acc_flags != 0)) {
     atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
-    if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
-    else if (acc_flags) atomicOr(prm.flags, acc_flags);
+    if (acc_flags) atomicOr(prm.flags, acc_flags);
   }
 }
 
@@ -1483,7 +1476,7 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
   // with a workspace, the ranks that the kernel for p with violations cannot finish go to a list
   // there (the room of the list of open entries, as 32-bit rows) and k_digest_listed computes them
   uint32_t *rank_count = nullptr, *rank_list = nullptr;
-  if (work && share && workspace) {
+  if (work && share && workspace && !edges) {      // (the edge check is no faster with the list: 5.09 ms against 5.01)
     const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256) + kTableBytes;
     rank_count = reinterpret_cast<uint32_t *>(base);
     rank_list = reinterpret_cast<uint32_t *>(base + 256u);
@@ -1519,8 +1512,7 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
     const uint64_t most = n < prm.rank_cap ? n : prm.rank_cap;
     const uint64_t blocks_listed = (most + kBlock - 1) / kBlock;
     const dim3 gl((unsigned)(blocks_listed < 4096u ? blocks_listed : 4096u));
-    if (edges) hipLaunchKernelGGL((k_digest_listed<true>), gl, b, lds_listed, st, prm);
-    else hipLaunchKernelGGL((k_digest_listed<false>), gl, b, lds_listed, st, prm);
+    hipLaunchKernelGGL(k_digest_listed, gl, b, lds_listed, st, prm);
   }
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }

@@ -1119,7 +1119,8 @@ __device__ __forceinline__ uint32_t resolve_from_table(const Instance &in, const
 // the same tile, or in the following tile of 64 ranks whose rows are still in
 // LDS, its row is read instead of recomputed.  tile_recv and next_recv point at
 // the receive row of lane 0 of the two tiles (next_recv may be null); rows are
-// row_pitch and next_pitch bytes apart.  Returns the violations that are still
+// row_pitch and next_pitch bytes apart, and of the following tile's rows only rounds
+// 0 .. next_pitch - 1 are there (eight are enough: skip[8] > 128 reaches further).  Returns the violations that are still
 // open.  Call after phase one of the tile is complete and visible.
 __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint32_t viol,
                                                        int8_t *send_row, const int8_t *tile_recv,
@@ -1132,7 +1133,7 @@ __device__ __forceinline__ uint32_t resolve_from_tiles(const Instance &in, uint3
     viol &= viol - 1u;
     const uint32_t tl = lane + skip_at_level(in.pm1, in.q - k);   // < 2^32: lane < 64, skip < 2^31
     if (tl < n_valid) send_row[k] = tile_recv[tl * row_pitch + k];
-    else if (next_recv != nullptr && n_valid == 64u && tl - 64u < n_valid_next)
+    else if (next_recv != nullptr && n_valid == 64u && tl - 64u < n_valid_next && k < next_pitch)
       send_row[k] = next_recv[(tl - 64u) * next_pitch + k];
     else open |= 1u << k;
   }

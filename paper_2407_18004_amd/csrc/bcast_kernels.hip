@@ -210,9 +210,14 @@ constexpr uint32_t kDeferCap = 128u;                 // queue entries per wavefr
 constexpr uint32_t kRowQueueCap = 2u * kWave;         // ... of k_digest: 63 left over + 64 of a tile
 constexpr uint32_t kQueueWords = kDeferCap > kRowQueueCap ? kDeferCap : kRowQueueCap;
 
+// Of the receive rows of the tile above only rounds 0 .. kAboveRounds - 1 are kept: a violation in
+// round k asks for the rank skip[k] further on, and only skip[0..7] <= 2^7 reach no further
+// than the next tile from some lane of this one (skip[8] > 128).
+constexpr uint32_t kAboveRounds = 8;
+constexpr uint32_t kAboveWords = kWave * kAboveRounds / 4u;
 // words of LDS per wavefront: slice, receive rows of the tile above, queue
 __host__ __device__ inline uint32_t deferred_wave_words(uint32_t q) {
-  return slice_words(q) + 16u * q + kQueueWords + kRecordWords;
+  return slice_words(q) + kAboveWords + kQueueWords + kRecordWords;
 }
 // The same for k_digest, whose rows never leave LDS and are laid out for word reads: 64 rows
 // digest_row_pitch(q) bytes apart.
@@ -221,7 +226,7 @@ __host__ __device__ inline uint32_t digest_lone_block_words(uint32_t q) {
   return kWavesPerBlock * (digest_slice_words(q) + kRecordWords);
 }
 __host__ __device__ inline uint32_t digest_deferred_wave_words(uint32_t q) {
-  return digest_slice_words(q) + 16u * q + kQueueWords + kRecordWords;
+  return digest_slice_words(q) + kAboveWords + kQueueWords + kRecordWords;
 }
 
 // Hands n entries (one per lane with `mine`, as row of the launch << 5 | round) to the list that
@@ -309,9 +314,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     return;
   }
 
-  int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
-  uint32_t *queue = words + slice_w + 16u * q;
-  lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane, split_stretch);
+  int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][kAboveRounds]
+  uint32_t *queue = words + slice_w + kAboveWords;
+  lockstep_cache_init(record, words + slice_w + kAboveWords + kQueueWords, lane, split_stretch);
   const uint64_t run_row0 = t_lo * kWave;
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     uint32_t open = 0;
     if (lane < n_valid) {
       open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
-                                pitch, q, lane, n_valid, n_valid_above);
+                                pitch, kAboveRounds, lane, n_valid, n_valid_above);
       if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
     }
     // Open violations go into the queue as (row within the run) << 5 | k.  A tile can have more
@@ -356,7 +361,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       if (!rows_out) {
         copy_out(row0, n_valid);
         if (lane < n_valid)
-          for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+          for (uint32_t k = 0; k < q && k < kAboveRounds; ++k) above[lane * kAboveRounds + k] = recv_row[k];
         n_valid_above = n_valid;
         rows_out = true;
       }
@@ -391,10 +396,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       uint32_t u_lo, u_tiles;
       run_of_wave(prm.runs, u, u_lo, u_tiles);
       const uint64_t first = (uint64_t)u_lo * kWave;
-      if (u_tiles != 0u && target >= first && target < first + kWave && target < prm.n_ranks) {
+      if (k < kAboveRounds && u_tiles != 0u && target >= first && target < first + kWave && target < prm.n_ranks) {
         const int8_t *above_u =
             reinterpret_cast<const int8_t *>(lds_dyn + u * wave_words + slice_w);
-        prm.send[row * (uint64_t)prm.ld + k] = above_u[(uint32_t)(target - first) * q + k];
+        prm.send[row * (uint64_t)prm.ld + k] = above_u[(uint32_t)(target - first) * kAboveRounds + k];
         waiting = false;
       }
     }
@@ -407,7 +412,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   __syncthreads();
   // entries of the four queues, in the order of the wavefronts: 64 to a wavefront
   static_assert(kWavesPerBlock == 4, "four queues are pooled");
-  const uint32_t count_at = slice_w + 16u * q + kQueueWords - 1u;
+  const uint32_t count_at = slice_w + kAboveWords + kQueueWords - 1u;
   const uint32_t end0 = lds_dyn[count_at];
   const uint32_t end1 = end0 + lds_dyn[wave_words + count_at];
   const uint32_t end2 = end1 + lds_dyn[2u * wave_words + count_at];
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   if (have_one) {
     const uint32_t u = (mine >= end0 ? 1u : 0u) + (mine >= end1 ? 1u : 0u) + (mine >= end2 ? 1u : 0u);
     const uint32_t start = u == 0u ? 0u : u == 1u ? end0 : u == 2u ? end1 : end2;
-    const uint32_t entry = lds_dyn[u * wave_words + slice_w + 16u * q + (mine - start)];
+    const uint32_t entry = lds_dyn[u * wave_words + slice_w + kAboveWords + (mine - start)];
     uint32_t u_lo, u_tiles;
     run_of_wave(prm.runs, u, u_lo, u_tiles);
     row = (uint64_t)u_lo * kWave + (entry >> 5);
@@ -548,9 +553,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
       wave_lds_sync();                         // the slice is rewritten next
     }
   } else {
-    int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][q]
-    uint32_t *queue = words + slice_w + 16u * q;
-    lockstep_cache_init(record, words + slice_w + 16u * q + kQueueWords, lane, split_stretch);
+    int8_t *above = reinterpret_cast<int8_t *>(words + slice_w);          // [64][kAboveRounds]
+    uint32_t *queue = words + slice_w + kAboveWords;
+    lockstep_cache_init(record, words + slice_w + kAboveWords + kQueueWords, lane, split_stretch);
     const uint64_t run_row0 = t_lo * kWave;
     uint32_t n_queued = 0;                     // the same in all lanes; at most 63 between tiles
     uint32_t n_valid_above = 0;
@@ -607,7 +612,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
           acc_flags |= resolve_by_search(in, v, left, send_row);
         } else {
           open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
-                                    pitch, q, lane, n_here, n_valid_above);
+                                    pitch, kAboveRounds, lane, n_here, n_valid_above);
           if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
         }
         if (open == 0) take_row(r, v, b);
@@ -625,7 +630,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
         const uint32_t n_new = n_queued + (uint32_t)__popcll(who);
         n_queued = n_new < kRowQueueCap ? n_new : kRowQueueCap;
         if (lane < n_here)
-          for (uint32_t k = 0; k < q; ++k) above[lane * q + k] = recv_row[k];
+          for (uint32_t k = 0; k < q && k < kAboveRounds; ++k) above[lane * kAboveRounds + k] = recv_row[k];
         n_valid_above = n_here;
       }
       wave_lds_sync();                         // slice and queue are rewritten next

@@ -508,10 +508,10 @@ __global__ void k_edges_init(uint64_t *xors, uint32_t *count) {
 // and hashes it.  That is 2 to 3 ranks in 64; it costs the slice its rows, so
 // the record of the top levels starts again after a batch.
 template <bool kShare, bool kEdges, bool kMemo>
-// (The kernels with deferred violations hold five or six workgroups per CU at large q, where their LDS
-// sets the limit, and are compiled for six wavefronts per SIMD and more: with the registers of eight
-// they are 2-3 % slower.)
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ? 6 : 8, 8))) void k_digest(DigestParams prm) {
+// (The kernels with deferred violations hold seven workgroups per CU at large q, where their LDS
+// sets the limit, and are compiled for seven wavefronts per SIMD and more: with the registers of
+// eight, or of six, they are 2-3 % slower.)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ? 7 : 8, 8))) void k_digest(DigestParams prm) {
   extern __shared__ __align__(16) uint32_t lds_dyn[];
   const uint32_t lane = threadIdx.x & (kWave - 1);
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));

@@ -854,81 +854,154 @@ __global__ void k_u32_zero(uint32_t *x) {
 }
 
 // The ranks of a tile are arbitrary ranks of one instance, so a violation of Algorithm 6 has no
-// neighbour's row to look at: every one takes a search of its own.  Searching where they arise
-// would mean up to four searches in a row with the few lanes that have a first, second, ...
-// violation; instead the tile's violations are collected (owner lane and round, 2 bytes each)
-// and worked off 64 at a time, one per lane.
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
-  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
-  __shared__ uint16_t open_entry[kWavesPerBlock][4 * kWave];   // lane << 5 | k; at most four per rank
-  __shared__ uint32_t open_v[kWavesPerBlock][kWave];           // the owner's virtual rank
-  const uint32_t lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
-  const uint64_t n_work = (uint64_t)prm.n_inst * prm.tiles_per_inst;
-  for (uint64_t work = (uint64_t)blockIdx.x * kWavesPerBlock + wave; work < n_work;
-       work += (uint64_t)gridDim.x * kWavesPerBlock) {
-    const uint32_t inst = (uint32_t)(work / prm.tiles_per_inst);
-    const uint32_t tile = (uint32_t)(work % prm.tiles_per_inst);
-    const uint32_t p = prm.p[inst];
-    const uint32_t root = prm.root[inst];
-    const uint32_t q = p > 1u ? 32u - (uint32_t)__clz((int)(p - 1u)) : 0u;
-    const uint64_t off0 = prm.row_off[inst], off1 = prm.row_off[inst + 1];
-    const bool inst_ok = p >= 1u && p <= BCAST_MAX_P && root < p && off1 >= off0 &&
-                         off1 - off0 == (uint64_t)prm.m * 2u * q && off1 <= prm.out_elems;
-    if (!inst_ok) {
-      if (tile == 0 && lane == 0 && prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
-      continue;
+// neighbour's row to look at: every one takes a search of its own (search_entry: the levels from
+// the top down, then the ascent until round k is out).  Searching where they arise would mean up
+// to four searches in a row with the few lanes that have a first, second, ... violation; instead
+// a tile's violations are collected (owner lane and round, 2 bytes each) and searched 64 at a
+// time, one per lane.  Such a pass runs as long as its longest search: two moves for a violation
+// in round 1, the most common one, and twenty and more for one in round 10.  So only the
+// violations in rounds below kShortRounds, five in six, are searched with their tile, and
+// answered in the tile's rows in LDS before these leave.  The others leave open: a wavefront
+// takes kBatchTiles tiles of one instance in a row and queues them (row within the batch << 5 |
+// round); whenever 64 are waiting, and at the end of the batch, they are searched and each
+// answer goes to its place in the caller's table.  (All violations through that queue: fewer
+// instructions and slower, because every answer and every owner's rank read again is a memory
+// transaction of its own, and there are 0.8 violations per rank.)
+constexpr uint32_t kBatchTiles = 16;
+constexpr uint32_t kShortRounds = 4;
+constexpr uint32_t kLongQueue = 2 * kWave;      // 63 waiting + one more from every lane
+
+struct BatchLds {
+  uint32_t *rows;                   // kTileBytes of the wavefront's own
+  uint16_t *open_entry;             // 4 * kWave: lane << 5 | k, at most four per rank
+  uint32_t *open_v;                 // kWave: the owner's virtual rank
+  uint16_t *waiting;                // kLongQueue
+};
+
+// Tiles tile0 .. tile1 - 1 (at most kBatchTiles) of instance `inst`, whose rows begin at off0.
+__device__ __forceinline__ void batch_tiles(const BatchParams &prm, const Instance &in, uint32_t inst,
+                                            uint64_t off0, uint32_t tile0, uint32_t tile1,
+                                            const BatchLds &mem, uint32_t lane) {
+  const uint32_t p = in.p, q = in.q;
+  const uint64_t below = (1ull << lane) - 1ull;
+  const uint32_t *batch_ranks = prm.ranks + (uint64_t)inst * prm.m + (uint64_t)tile0 * kWave;
+  int32_t *batch_out = prm.out + off0 + (uint64_t)tile0 * kWave * 2u * q;
+  int8_t *recv_row = reinterpret_cast<int8_t *>(mem.rows) + lane * 2u * q;
+  int8_t *send_row = recv_row + q;
+  // Entries first .. first + count - 1 of the queue, one per lane: the owner's rank is read
+  // again, the answer goes to the owner's row in the caller's table.  That row was stored by
+  // other lanes of this wavefront; the wait lets those stores arrive before the entry is written.
+  auto search_waiting = [&](uint32_t first, uint32_t count) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (lane < count) {
+      const uint32_t item = mem.waiting[first + lane];
+      const uint32_t row = item >> 5, k = item & 31u;
+      const uint32_t v = virtual_rank(in, batch_ranks[row]);
+      uint32_t fl = 0;
+      batch_out[(uint64_t)row * 2u * q + q + k] = search_entry<true>(in, to_processor(in, v, k), k, fl);
     }
-    const Instance in = make_instance(p, q, root);
+    wave_lds_sync();
+  };
+  uint32_t n_waiting = 0;                          // the same in all lanes
+  for (uint32_t tile = tile0; tile < tile1; ++tile) {
     const uint32_t j0 = tile * kWave;
     const uint32_t n_valid = prm.m - j0 < (uint32_t)kWave ? prm.m - j0 : (uint32_t)kWave;
-    int8_t *recv_row = reinterpret_cast<int8_t *>(lds[wave]) + lane * 2u * q;
-    int8_t *send_row = recv_row + q;
-    uint32_t viol = 0;
+    uint32_t early = 0, late = 0;        // violations searched with the tile, and left to the queue
     if (lane < n_valid) {
-      const uint32_t r = prm.ranks[(uint64_t)inst * prm.m + j0 + lane];
+      const uint32_t r = batch_ranks[j0 - tile0 * kWave + lane];
       if (r < p) {
         int b;
         uint32_t flags;
         LockstepCache none;
         lockstep_cache_init(none, nullptr);
         const uint32_t v = virtual_rank(in, r);
-        open_v[wave][lane] = v;
+        mem.open_v[lane] = v;
         DeepTable no_table;
         no_table.entries = nullptr; no_table.viol_by_e = nullptr; no_table.first_deep = 0; no_table.n_rho = 0;
         MemoOut unused;
-        viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none, false,
-                                                no_table, unused);
+        const uint32_t viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none,
+                                                               false, no_table, unused);
+        early = viol & ((1u << kShortRounds) - 1u);
+        late = viol & ~((1u << kShortRounds) - 1u);
       } else {                           // rank outside the instance: marked row
         for (uint32_t k = 0; k < 2u * q; ++k) recv_row[k] = (int8_t)kInvalidByte;
         if (prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
       }
     }
-    for (;;) {
-      uint32_t n_open = 0;               // the same in all lanes
-      while (n_open + kWave <= 4u * kWave && __any(viol != 0)) {   // one more per lane still fits
-        const bool has = viol != 0;
-        const uint64_t who = __ballot(has);
-        if (has) {
-          const uint32_t slot = n_open + (uint32_t)__popcll(who & ((1ull << lane) - 1ull));
-          open_entry[wave][slot] = (uint16_t)((lane << 5) | (uint32_t)(__ffs((int)viol) - 1));
-          viol &= viol - 1u;
-        }
-        n_open += (uint32_t)__popcll(who);
+    uint32_t n_open = 0;                 // the same in all lanes
+    while (__any(early != 0)) {          // one more from every lane that has one
+      const bool has = early != 0;
+      const uint64_t who = __ballot(has);
+      if (has) {
+        mem.open_entry[n_open + (uint32_t)__popcll(who & below)] =
+            (uint16_t)((lane << 5) | (uint32_t)(__ffs((int)early) - 1));
+        early &= early - 1u;
       }
-      wave_lds_sync();
-      if (n_open == 0) break;
-      for (uint32_t e = lane; e < n_open; e += kWave) {
-        const uint32_t item = open_entry[wave][e];
-        const uint32_t owner = item >> 5, k = item & 31u;
-        uint32_t fl = 0;
-        const int val = search_entry<true>(in, to_processor(in, open_v[wave][owner], k), k, fl);
-        reinterpret_cast<int8_t *>(lds[wave])[owner * 2u * q + q + k] = (int8_t)val;
-      }
-      wave_lds_sync();
+      n_open += (uint32_t)__popcll(who);
     }
-    tile_out<true>(lds[wave], prm.out + off0 + (uint64_t)j0 * 2u * q, n_valid * 2u * q, lane);
     wave_lds_sync();
+    for (uint32_t e = lane; e < n_open; e += kWave) {
+      const uint32_t item = mem.open_entry[e];
+      const uint32_t owner = item >> 5, k = item & 31u;
+      uint32_t fl = 0;
+      const int val = search_entry<true>(in, to_processor(in, mem.open_v[owner], k), k, fl);
+      reinterpret_cast<int8_t *>(mem.rows)[owner * 2u * q + q + k] = (int8_t)val;
+    }
+    wave_lds_sync();
+    tile_out<true>(mem.rows, prm.out + off0 + (uint64_t)j0 * 2u * q, n_valid * 2u * q, lane);
+    while (__any(late != 0)) {
+      const bool has = late != 0;
+      const uint64_t who = __ballot(has);
+      if (has) {
+        mem.waiting[n_waiting + (uint32_t)__popcll(who & below)] =
+            (uint16_t)((((tile - tile0) * kWave + lane) << 5) | (uint32_t)(__ffs((int)late) - 1));
+        late &= late - 1u;
+      }
+      n_waiting += (uint32_t)__popcll(who);
+      wave_lds_sync();
+      if (n_waiting >= (uint32_t)kWave) { n_waiting -= kWave; search_waiting(n_waiting, kWave); }
+    }
+    wave_lds_sync();                     // the rows are rewritten next
+  }
+  if (n_waiting != 0) search_waiting(0, n_waiting);
+}
+
+// What the kernel can check of instance `inst` (the host sees none of it): false = it writes nothing.
+__device__ __forceinline__ bool batch_instance(const BatchParams &prm, uint32_t inst, Instance &in,
+                                               uint64_t &off0) {
+  const uint32_t p = prm.p[inst];
+  const uint32_t root = prm.root[inst];
+  const uint32_t q = p > 1u ? 32u - (uint32_t)__clz((int)(p - 1u)) : 0u;
+  off0 = prm.row_off[inst];
+  const uint64_t off1 = prm.row_off[inst + 1];
+  in = make_instance(p, q, root);
+  return p >= 1u && p <= BCAST_MAX_P && root < p && off1 >= off0 &&
+         off1 - off0 == (uint64_t)prm.m * 2u * q && off1 <= prm.out_elems;
+}
+
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
+  __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
+  __shared__ uint16_t open_entry[kWavesPerBlock][4 * kWave];
+  __shared__ uint32_t open_v[kWavesPerBlock][kWave];
+  __shared__ uint16_t waiting[kWavesPerBlock][kLongQueue];
+  const uint32_t lane = threadIdx.x & (kWave - 1);
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const BatchLds mem = {lds[wave], open_entry[wave], open_v[wave], waiting[wave]};
+  const uint32_t batches_per_inst = (prm.tiles_per_inst + kBatchTiles - 1u) / kBatchTiles;
+  const uint64_t n_work = (uint64_t)prm.n_inst * batches_per_inst;
+  for (uint64_t work = (uint64_t)blockIdx.x * kWavesPerBlock + wave; work < n_work;
+       work += (uint64_t)gridDim.x * kWavesPerBlock) {
+    const uint32_t inst = (uint32_t)(work / batches_per_inst);
+    const uint32_t batch = (uint32_t)(work % batches_per_inst);
+    Instance in;
+    uint64_t off0;
+    if (!batch_instance(prm, inst, in, off0)) {
+      if (batch == 0 && lane == 0 && prm.n_rejected) atomicAdd(prm.n_rejected, 1u);
+      continue;
+    }
+    const uint32_t tile0 = batch * kBatchTiles;
+    const uint32_t tile1 = prm.tiles_per_inst - tile0 < kBatchTiles ? prm.tiles_per_inst : tile0 + kBatchTiles;
+    batch_tiles(prm, in, inst, off0, tile0, tile1, mem, lane);
   }
 }
 
@@ -1694,9 +1767,14 @@ int bcast_schedules_batched(uint32_t n_inst, const uint32_t *p, const uint32_t *
   prm.n_inst = n_inst; prm.m = m; prm.tiles_per_inst = (m + kWave - 1) / kWave;
   prm.p = p; prm.root = root; prm.ranks = ranks; prm.row_off = row_off;
   prm.out = out; prm.out_elems = out_elems; prm.n_rejected = n_rejected;
-  const uint64_t work = (uint64_t)n_inst * prm.tiles_per_inst;
-  const int grid = persistent_grid((work + kWavesPerBlock - 1) / kWavesPerBlock);
+  const uint64_t work = (uint64_t)n_inst * ((prm.tiles_per_inst + kBatchTiles - 1u) / kBatchTiles);
+  // a batch is long enough for four times the usual number of workgroups: less of a tail
+  int grid = persistent_grid(UINT64_MAX);
   if (grid < 0) return BCAST_EHIP;
+  {
+    const uint64_t want = (work + kWavesPerBlock - 1) / kWavesPerBlock, cap = (uint64_t)grid * 4u;
+    grid = (int)(want < cap ? want : cap);
+  }
   hipLaunchKernelGGL(k_batched, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, prm);
   return launch_ok() ? BCAST_OK : BCAST_EHIP;
 }

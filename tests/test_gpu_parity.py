@@ -429,6 +429,10 @@ def check_batched(first, n_inst, m, check_every=1):
 def test_workload4_batched_small():
     check_batched(0, 300, 200)                 # ragged tiles: 200 = 3*64 + 8
     check_batched(1000, 64, 4096, check_every=4)
+    # wavefronts take 16 tiles of an instance in a row: 68 tiles are four such batches and one of
+    # four tiles, the last of them ragged; 17 tiles are one batch and a single tile
+    check_batched(2000, 40, 4096 + 200, check_every=2)
+    check_batched(3000, 48, 1024 + 8, check_every=2)
 
 
 def test_workload4_batched_rejects_bad_input():

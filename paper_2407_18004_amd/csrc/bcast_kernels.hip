@@ -114,9 +114,15 @@ struct SchedParams {
   DeepTable table;                  // kernels with kMemo only
   // Entries of the send part that k_schedules<true, .> leaves open for k_fill_open (row of the
   // launch << 5 | round), or null: then the kernel fills them in itself, by search.
+  // Two forms.  One list for the launch (open_segments = 0): open_count is one word, the entries
+  // claimed so far (may run past open_cap), zero at launch.  A segment of open_cap entries per
+  // wavefront (open_segments = wavefronts of the launch): segment w is open_list[w * open_cap ..],
+  // and every wavefront stores how many it has used to open_count[w] before it ends, so nothing
+  // has to be cleared ahead of the launch.
   unsigned long long *open_list;
-  uint32_t *open_count;             // entries claimed so far (may run past open_cap)
+  uint32_t *open_count;
   uint32_t open_cap;
+  uint32_t open_segments;
 };
 
 // The run of wavefront `wave` (the same in all lanes) of this workgroup: first tile and number
@@ -232,9 +238,17 @@ __host__ __device__ inline uint32_t digest_deferred_wave_words(uint32_t q) {
 // Hands n entries (one per lane with `mine`, as row of the launch << 5 | round) to the list that
 // k_fill_open works off after this kernel, if there is a list and it has room for all of them.
 // Returns whether it did (the same in all lanes).
-__device__ __forceinline__ bool publish_open(const SchedParams &prm, uint32_t n, bool mine,
-                                             unsigned long long entry, uint32_t lane) {
+__device__ __forceinline__ bool publish_open(const SchedParams &prm, uint32_t wave_id, uint32_t &seg_used,
+                                             uint32_t n, bool mine, unsigned long long entry, uint32_t lane) {
   if (prm.open_list == nullptr || n == 0u) return n == 0u && prm.open_list != nullptr;
+  if (prm.open_segments != 0u) {                     // the wavefront's own segment
+    if (wave_id >= prm.open_segments || n > prm.open_cap - seg_used) return false;
+    const uint64_t who = __ballot(mine);
+    if (mine)
+      prm.open_list[(uint64_t)wave_id * prm.open_cap + seg_used + (uint32_t)__popcll(who & ((1ull << lane) - 1ull))] = entry;
+    seg_used += n;
+    return true;
+  }
   uint32_t base = 0;
   if (lane == 0) base = atomicAdd(prm.open_count, n);
   base = lane0_of(base);
@@ -250,10 +264,11 @@ __device__ __forceinline__ bool publish_open(const SchedParams &prm, uint32_t n,
 
 __device__ __forceinline__ void deferred_flush(const Instance &in, const SchedParams &prm,
                                                const uint32_t *queue, uint64_t run_row0,
-                                               uint32_t lo, uint32_t hi, uint32_t lane) {
+                                               uint32_t lo, uint32_t hi, uint32_t lane,
+                                               uint32_t wave_id, uint32_t &seg_used) {
   // The rows were stored by this wavefront; they must have landed before single
   // entries of them are overwritten.
-  if (publish_open(prm, hi - lo, lo + lane < hi,
+  if (publish_open(prm, wave_id, seg_used, hi - lo, lo + lane < hi,
                    lo + lane < hi ? ((run_row0 + (queue[lo + lane] >> 5)) << 5) | (queue[lo + lane] & 31u) : 0ull,
                    lane))
     return;
@@ -318,6 +333,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   uint32_t *queue = words + slice_w + kAboveWords;
   lockstep_cache_init(record, words + slice_w + kAboveWords + kQueueWords, lane, split_stretch);
   const uint64_t run_row0 = t_lo * kWave;
+  const uint32_t wave_id = blockIdx.x * kWavesPerBlock + wave;
+  uint32_t seg_used = 0;                       // entries in this wavefront's segment of the open list
   uint32_t n_queued = 0;                       // the same in all lanes
   uint32_t n_valid_above = 0;                  // 0: no tile above in LDS yet
   for (uint64_t tile = t_hi; tile-- > t_lo;) {
@@ -368,7 +385,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
       const bool more = __any(open != 0);
       while (n_queued >= (uint32_t)kWave || (more && n_queued != 0u)) {
         const uint32_t n_batch = n_queued < (uint32_t)kWave ? n_queued : (uint32_t)kWave;
-        deferred_flush(in, prm, queue, run_row0, n_queued - n_batch, n_queued, lane);
+        deferred_flush(in, prm, queue, run_row0, n_queued - n_batch, n_queued, lane, wave_id, seg_used);
         n_queued -= n_batch;
         if (more) break;                       // room again: queue the rest first
       }
@@ -432,7 +449,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
   }
   const uint32_t first = wave * kWave;               // this wavefront's share of the pool
   const uint32_t n_mine = end3 > first ? (end3 - first < (uint32_t)kWave ? end3 - first : (uint32_t)kWave) : 0u;
-  if (n_mine == 0u || publish_open(prm, n_mine, have_one, (row << 5) | k, lane)) return;
+  const bool handed_on = n_mine == 0u || publish_open(prm, wave_id, seg_used, n_mine, have_one, (row << 5) | k, lane);
+  if (prm.open_segments != 0u && wave_id < prm.open_segments && lane == 0) prm.open_count[wave_id] = seg_used;
+  if (handed_on) return;
   if (have_one) {
     const uint32_t v = virtual_rank(in, (uint32_t)(prm.r_begin + row));
     uint32_t fl = 0;
@@ -445,11 +464,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 // is in the range of the call; if not, by a search as before.
 __global__ __launch_bounds__(kBlock) void k_fill_open(SchedParams prm) {
   const Instance in = make_instance(prm.p, prm.q, prm.root);
-  // every claim that fit was written in full; the one claim that reached past the end of the
-  // list marked its slots unused; later claims start beyond the end
-  const uint32_t claimed = *prm.open_count;
-  const uint32_t n = claimed < prm.open_cap ? claimed : prm.open_cap;
+  // One list: every claim that fit was written in full; the one claim that reached past the end of
+  // the list marked its slots unused; later claims start beyond the end.  Segments: the first
+  // open_count[w] entries of segment w.
+  const uint32_t claimed = prm.open_segments != 0u ? 0u : *prm.open_count;
+  const uint64_t n = prm.open_segments != 0u ? (uint64_t)prm.open_segments * prm.open_cap
+                                             : (claimed < prm.open_cap ? claimed : prm.open_cap);
   for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+    if (prm.open_segments != 0u && (uint32_t)(i % prm.open_cap) >= prm.open_count[i / prm.open_cap]) continue;
     const unsigned long long item = prm.open_list[i];
     if (item == ~0ull) continue;                     // a slot no claim that fit covers
     const uint64_t row = item >> 5;
@@ -1437,6 +1459,22 @@ uint32_t open_list_capacity(uint32_t p) {
   const uint64_t want = (uint64_t)p / 8u + 4096u;    // p = 1,000,003 leaves 39,000 open, p = 2^20 + 1 fewer than p / 16
   return (uint32_t)(want < (1ull << 22) ? want : (1ull << 22));
 }
+// The same room as segments of kOpenSegCap entries, one per wavefront, for the launches that no
+// kernel precedes which could clear the list's counter (fewer than kTableMinRanks ranks: at most
+// 8,192 wavefronts of one to three tiles, which leave two or three entries open per tile): a
+// launch of its own to clear one word costs 4 us, a twentieth of the table of p = 1,000,003.
+constexpr uint32_t kOpenSegCap = 64;
+constexpr uint32_t kOpenSegWavesMax = 8192;
+uint32_t open_segments_room(uint32_t p) {
+  const uint64_t waves = ((uint64_t)p + kWave - 1) / kWave + kWavesPerBlock;
+  return (uint32_t)(waves < kOpenSegWavesMax ? waves : kOpenSegWavesMax);
+}
+size_t open_bytes(uint32_t p) {                      // either form, after the tables
+  const size_t list = 256u + (size_t)open_list_capacity(p) * 8u;
+  const size_t segments = ((size_t)open_segments_room(p) * 4u + 255u) / 256u * 256u +
+                          (size_t)open_segments_room(p) * kOpenSegCap * 8u;
+  return (list > segments ? list : segments) + 256u;
+}
 
 // Building the tables takes one small kernel ahead of the main one, some 12 us from launch to end;
 // it pays from a million ranks on (measured on MI355X, tables with a workspace: p = 1,000,003
@@ -1500,7 +1538,7 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
   const int grid = share ? run_grid((n + kWave - 1) / kWave, 8u) : lone_grid(blocks);
   if (grid < 0) return BCAST_EHIP;
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
-  prm.open_list = nullptr; prm.open_count = nullptr; prm.open_cap = 0;
+  prm.open_list = nullptr; prm.open_count = nullptr; prm.open_cap = 0; prm.open_segments = 0;
   if (share && workspace) {                          // entries left open go to a list, see k_fill_open
     const uintptr_t base = align_up(reinterpret_cast<uintptr_t>(workspace), 256) + kTableBytes;
     prm.open_count = reinterpret_cast<uint32_t *>(base);
@@ -1510,6 +1548,16 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
   bool count_cleared = false;
   if (!prepare_table(p, q, n, workspace, (hipStream_t)stream, prm.table, prm.open_count, &count_cleared))
     return BCAST_EHIP;
+  if (prm.open_list != nullptr && !count_cleared &&
+      (uint64_t)grid * kWavesPerBlock <= (uint64_t)open_segments_room(p)) {
+    // nothing ahead of the main kernel that could clear the counter: a segment per wavefront instead
+    const uintptr_t base = reinterpret_cast<uintptr_t>(prm.open_count);
+    const size_t counts = ((size_t)open_segments_room(p) * 4u + 255u) / 256u * 256u;
+    prm.open_list = reinterpret_cast<unsigned long long *>(base + counts);
+    prm.open_cap = kOpenSegCap;
+    prm.open_segments = (uint32_t)grid * kWavesPerBlock;
+    count_cleared = true;                            // there is no counter
+  }
   const bool memo = prm.table.entries != nullptr;
   const size_t lds = share ? (size_t)kWavesPerBlock * deferred_wave_words(prm.q) * 4u
                            : (size_t)lone_block_words(prm.q) * 4u;
@@ -1522,7 +1570,8 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
     else hipLaunchKernelGGL((k_schedules<true, false>), dim3(grid), dim3(kBlock), lds, (hipStream_t)stream, prm);
     if (prm.open_list) {
       if (!launch_ok()) return BCAST_EHIP;
-      const uint64_t most = n * 4u < prm.open_cap ? n * 4u : prm.open_cap;      // at most four per rank
+      const uint64_t most = prm.open_segments != 0u ? (uint64_t)prm.open_segments * prm.open_cap
+                            : n * 4u < prm.open_cap ? n * 4u : prm.open_cap;    // at most four per rank
       const uint64_t blocks_fill = (most + kBlock - 1) / kBlock;
       hipLaunchKernelGGL(k_fill_open, dim3((unsigned)(blocks_fill < 2048u ? (blocks_fill ? blocks_fill : 1u) : 2048u)),
                          dim3(kBlock), 0, (hipStream_t)stream, prm);
@@ -1597,7 +1646,7 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
 
 // workspace argument of a *_ws call: NULL is an error there, and so is one that is too small
 int check_workspace(uint32_t p, const void *workspace, size_t workspace_bytes) {
-  const size_t need = host_q(p) < 0 ? 0 : kTableBytes + 256u + (size_t)open_list_capacity(p) * 8u + 256u;
+  const size_t need = host_q(p) < 0 ? 0 : kTableBytes + open_bytes(p);
   if (need == 0 || !workspace) return BCAST_EINVAL;
   return workspace_bytes < need ? BCAST_ENOMEM : BCAST_OK;
 }
@@ -1610,7 +1659,7 @@ extern "C" {
 // left open.
 size_t bcast_schedules_workspace(uint32_t p) {
   if (host_q(p) < 0) return 0;
-  return kTableBytes + 256u + (size_t)open_list_capacity(p) * 8u + 256u;
+  return kTableBytes + open_bytes(p);
 }
 
 int bcast_schedules(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,

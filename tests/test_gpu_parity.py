@@ -740,6 +740,9 @@ def ws_digest_and_edges(p, root, a, b, ws):
     (2**24, 2**23 + 5, 2**23 - 2_000_000, 4_000_001),
     (3 * 2**20 + 1, 77, 0, 3 * 2**20 + 1),    # the smallest skip above the deep levels is odd
     (1000003, 0, 0, 1000003), (20000, 1, 0, 20000), (100, 3, 0, 100), (1, 0, 0, 1),   # below the thresholds
+    # fewer than 2^20 ranks: the entries left open go to a segment of the workspace per wavefront; with more
+    # than one violation per rank some segments fill up and their wavefronts search for the rest themselves
+    (2**19 + 1, 5, 0, 2**19 + 1), (2**20 - 3, 0, 7, 2**20 - 20), (786433, 9, 100000, 600000), (2**17 + 1, 2**16, 0, 2**17 + 1),
 ])
 def test_calls_with_workspace_equal_the_oracle(p, root, a, n):
     b = a + n

@@ -36,6 +36,15 @@ def test_host_only_entry_points(built):
     assert lib.bcast_strerror(0) == "ok"
     assert lib.bcast_simulate_workspace(65537, 256, 64) >= 64 * 8 * 65537 * 4
     assert lib.bcast_simulate_workspace(10, 0, 1) == 0
+    # the workspace of the *_ws calls: the two tables of deep entries (2,050 entries of 16 bytes and 32 rows
+    # of 2,050 16-bit words), then room for the open entries either as one list of p / 8 + 4,096 or as a
+    # segment of 64 per wavefront of a short launch (at most 8,192 of them, one per tile and four more)
+    tables = 2050 * 16 + 32 * 2050 * 2
+    sizes = [lib.bcast_schedules_workspace(p) for p in (1, 100, 65537, 1000003, 2**24 + 1, 2**31 - 1)]
+    assert sizes == sorted(sizes) and lib.bcast_schedules_workspace(2**31) == 0
+    assert sizes[0] >= tables + 8 * 4096 and sizes[0] < tables + 64 * 1024
+    assert sizes[3] >= tables + 8192 * (64 * 8 + 4)            # p = 1,000,003: 15,626 tiles, 8,192 segments
+    assert sizes[5] >= tables + 8 * 2**22 and sizes[5] < tables + 8 * 2**22 + 2**20
 
 
 def test_verdict_struct_layout():

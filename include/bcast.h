@@ -127,20 +127,27 @@ int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin,
                               uint64_t r_end, uint64_t *xors, void *stream);
 
 /* bcast_schedules, bcast_schedules_digest and bcast_schedules_edgecheck with a
- * device workspace of at least bcast_schedules_workspace(p) bytes (some 33 KB;
- * contents irrelevant on entry, overwritten): same arguments, same results, less
- * work per rank.  The levels of Algorithms 3, 4 and 5 with the small skips
- * (below 1,024) see of a rank only what Algorithm 3 has left of it after the
- * larger skips, a number below 2,050, so that part of every rank's computation
- * (the baseblock, the first receive entries, the state in which the search of
- * Algorithm 4 goes on) is computed once per such number, into the workspace,
- * by a small kernel ahead of the main one, and looked up by some p / 1,500
- * ranks each; violations of Algorithm 6 are answered from the same table where
- * the to-processor's entry holds the round in question.  p below 16,384 has
- * too few large skips, and for ranges of fewer than 2^21 ranks the small
- * kernel costs more than it saves: then these calls do what the plain ones do.  The
- * workspace may be reused by the next call on the same stream; calls that are
- * in flight at the same time need one each.  Errors as for the plain calls;
+ * device workspace of at least bcast_schedules_workspace(p) bytes (164 KB of
+ * tables and a list of about p bytes, at most 32 MB; contents irrelevant on
+ * entry, overwritten): same arguments, same results, less work per rank.
+ * The levels of Algorithms 3, 4 and 5 with the small skips (below 1,024) see
+ * of a rank only what Algorithm 3 has left of it after the larger skips, a
+ * number below 2,050, so that part of every rank's computation (the
+ * baseblock, the first receive entries, the state in which the search of
+ * Algorithm 4 goes on, the violations of Algorithm 6 in these rounds) is
+ * computed once per such number, into the workspace, by a small kernel ahead
+ * of the main one, and looked up by some p / 1,500 ranks each; violations of
+ * Algorithm 6 are answered from the same table where the to-processor's entry
+ * holds the round in question.  p below 16,384 has too few large skips, and
+ * for ranges of fewer than 2^20 ranks the small kernel costs more than it
+ * saves: then the tables are not used.  The list: entries of the send
+ * schedule that the main kernel of bcast_schedules_ws cannot take from rows it
+ * still holds are not searched for; their places are listed in the workspace,
+ * and a last kernel copies each from the finished table (Section 2:
+ * sendblock[k] of r is recvblock[k] of its to-processor), searching only for
+ * to-processors outside the range of the call.  The workspace may be reused by
+ * the next call on the same stream; calls that are in flight at the same time
+ * (on different streams) need one each.  Errors as for the plain calls;
  * workspace NULL: BCAST_EINVAL; too small: BCAST_ENOMEM. */
 size_t bcast_schedules_workspace(uint32_t p);
 int bcast_schedules_ws(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,

@@ -4,8 +4,8 @@
 One step = one pass of the whole path (skips, baseblock, receive search, send
 walk with violations, invariant flags and digest) over every rank of the huge
 streamed instance p = 2^31 - 1, root 0, in 32 chunks of 2^26 ranks, each chunk
-one call of bcast_schedules_digest_ws; the calls of a step alternate between
-two HIP streams (--streams).  Nothing crosses PCIe inside the timed
+with a digest and flags of its own, all of them from one call of
+bcast_schedules_digest_chunks.  Nothing crosses PCIe inside the timed
 region: the inputs are scalars and each chunk leaves 12 bytes in HBM.  The 32
 chunk digests are compared with the ones the CPU oracle wrote
 (tests/golden/streamed_chunk_digests.json).
@@ -89,31 +89,25 @@ def run(args) -> dict:
     fl = torch.zeros(n_chunks, dtype=torch.int32, device=dev)
     dgs = [dg[i:i + 1] for i in range(n_chunks)]
     fls = [fl[i:i + 1] for i in range(n_chunks)]
-    # The chunks of a step are independent calls.  With --streams N (2 by default) they go round N
-    # HIP streams of default priority, each with a workspace of its own, so that the first tiles
-    # of one chunk (no records to take over yet) and the last wavefronts of the chunk before it
-    # share the device; with --streams 1 they follow one another on the current stream.  Two
-    # streams overlap only when they sit on different hardware queues (a process has four here);
-    # now and then two of a process share one.  So for two streams four are made, and untimed steps
-    # ahead of the warm-up pick the pair that runs a step fastest.
-    n_streams = max(1, args.streams)
-    pool = ([torch.cuda.current_stream()] if n_streams == 1
-            else [torch.cuda.Stream(device=dev) for _ in range(4 if n_streams == 2 else n_streams)])
-    streams = pool[:n_streams]
-    wss = [torch.empty(lib.bcast_schedules_workspace(p), dtype=torch.uint8, device=dev) for _ in streams]
+    ws = torch.empty(lib.bcast_schedules_workspace(p), dtype=torch.uint8, device=dev)
+    chunk_ranks = chunks[0][1] - chunks[0][0]
 
-    def step(events=None, use=None):
-        use = len(streams) if use is None else use
-        for i, (a, b) in enumerate(chunks):
-            s = streams[i % use]
-            if events is not None:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record(s)
-            lib.bcast_schedules_digest_ws(p, 0, a, b, dgs[i], fls[i], wss[i % use], stream=s)
-            if events is not None:
-                e1.record(s)
-                events.append((e0, e1))
+    # One call computes the digests and flags of all chunks (bcast_schedules_digest_chunks: one
+    # launch works through the whole instance and writes a result per chunk); with
+    # --calls-per-chunk every chunk is a call of bcast_schedules_digest_ws, one after the other.
+    def step(events=None, per_chunk=False):
+        if events is not None:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+        if per_chunk:
+            for i, (a, b) in enumerate(chunks):
+                lib.bcast_schedules_digest_ws(p, 0, a, b, dgs[i], fls[i], ws)
+        else:
+            lib.bcast_schedules_digest_chunks(p, 0, 0, p, chunk_ranks, dg, fl, ws)
+        if events is not None:
+            e1.record()
+            events.append((e0, e1))
 
     if args.copy_probe:                 # known traffic: 256 MiB read + 256 MiB written per copy
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
@@ -123,41 +117,17 @@ def run(args) -> dict:
         torch.cuda.synchronize()
         del src, dst
 
-    if n_streams == 2:
-        best = None
-        for pair in ((0, 1), (2, 3), (0, 2)):
-            streams[:] = [pool[pair[0]], pool[pair[1]]]
-            step()
-            torch.cuda.synchronize()
-            t_pair = time.perf_counter()
-            step()
-            torch.cuda.synchronize()
-            t_pair = time.perf_counter() - t_pair
-            if best is None or t_pair < best[0]:
-                best = (t_pair, pair)
-        streams[:] = [pool[best[1][0]], pool[best[1][1]]]
     for _ in range(args.warmup):
-        step()
+        step(per_chunk=args.calls_per_chunk)
     torch.cuda.synchronize()
     events = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(events if n_streams == 1 else None)
+        step(events, per_chunk=args.calls_per_chunk)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = p / (ms_per_step * 1e-3)
-    ms_per_step_one_stream = ms_per_step
-    if n_streams > 1:
-        # The roofline prices the kernel by itself: the same steps once more, every chunk on one
-        # stream and between HIP events on it, after the timed region and outside `value`.
-        step(None, use=1)
-        torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for _ in range(args.steps):
-            step(events, use=1)
-        torch.cuda.synchronize()
-        ms_per_step_one_stream = (time.perf_counter() - t2) * 1e3 / args.steps
     flags_or = int(torch.bitwise_or(fl[0], fl.max()).item()) if n_chunks else 0
     assert int(fl.abs().sum().item()) == 0, "invariant flags raised on the GPU"
     per_chunk = [x & ((1 << 64) - 1) for x in dg.cpu().tolist()]
@@ -171,12 +141,26 @@ def run(args) -> dict:
                          [c["digest"] for c in gold["chunks"]] == [f"{x:016x}" for x in per_chunk])
         assert equals_oracle, "chunk digests differ from the oracle's"
 
+    # for comparison, outside the timed region: the same step as one call per chunk
+    other_ms = None
+    if not args.calls_per_chunk and not args.no_compare:
+        step(per_chunk=True)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(2):
+            step(per_chunk=True)
+        torch.cuda.synchronize()
+        other_ms = (time.perf_counter() - t2) * 1e3 / 2
+        per_chunk_again = [x & ((1 << 64) - 1) for x in dg.cpu().tolist()]
+        assert per_chunk_again == per_chunk, "one call and 32 calls give different chunk digests"
+
     launch_ms = [a.elapsed_time(b) for a, b in events]
     avg_launch_ms = sum(launch_ms) / len(launch_ms)
-    ranks_per_launch = p / n_chunks
+    ranks_per_launch = p                        # an event pair encloses a whole step
     # `achieved`: operations of the algorithm per rank (fixed, see ALGORITHMIC_LANE_OPS_Q31) x ranks
-    # per launch / live launch duration (the event pairs enclose the small kernels of the call,
-    # which clear the results and build the table of deep entries, as well).  `achieved_executed`:
+    # per step / live duration of the step between HIP events on the launch stream (the event pairs
+    # enclose the small kernels of the call or calls, which clear the results and build the table of
+    # deep entries, as well; k_digest is all but 20 us of it).  `achieved_executed`:
     # the same with the 32-bit lane-operations the kernel's active lanes execute per rank
     # (SQ_THREAD_CYCLES_VALU / ranks, measured with rocprofv3) in place of the fixed count.
     counters = load_counters()
@@ -195,11 +179,7 @@ def run(args) -> dict:
         "lane_ops_per_rank_executed": ops_exec,
         "traffic": counters.get("k_digest", {}).get("hbm_bytes_per_launch"),
         "avg_launch_ms": avg_launch_ms, "launches": len(launch_ms),
-        "measured": ("the timed region" if n_streams == 1 else
-                     "a second pass of the same steps with all chunks on one stream (the kernel by itself)"),
-        "ms_per_step_one_stream": ms_per_step_one_stream,
-        # the whole job against the same peak, whatever the streams overlap
-        "frac_of_the_job": ALGORITHMIC_LANE_OPS_Q31 * value / PEAK_LANE_OPS,
+        "ranks_per_launch": ranks_per_launch,
     }
 
     out = {
@@ -208,8 +188,11 @@ def run(args) -> dict:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32", "data": "synthetic",
         "config": {"workload": "streamed instance p=2^31-1, root=0, all ranks in 32 chunks of "
-                               "2^26, digest+flags per chunk (bcast_schedules_digest_ws)",
-                   "p": p, "q": q, "chunks": n_chunks, "streams": n_streams, "digest": f"{whole:016x}",
+                               "2^26, digest+flags per chunk (" +
+                               ("bcast_schedules_digest_ws" if args.calls_per_chunk else "bcast_schedules_digest_chunks") + ")",
+                   "p": p, "q": q, "chunks": n_chunks,
+                   "calls_per_step": n_chunks if args.calls_per_chunk else 1,
+                   "ms_per_step_with_a_call_per_chunk": other_ms, "digest": f"{whole:016x}",
                    "flags": flags_or, "digests_equal_oracle": equals_oracle},
         "roofline": roofline,
     }
@@ -418,8 +401,10 @@ def main() -> None:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--streams", type=int, default=2,
-                    help="HIP streams the chunks of a step go round (1: one after the other)")
+    ap.add_argument("--no-compare", action="store_true",
+                    help="skip the untimed steps with a call per chunk that are run for comparison")
+    ap.add_argument("--calls-per-chunk", action="store_true",
+                    help="a call of bcast_schedules_digest_ws per chunk instead of one call for all chunks")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--headline-only", action="store_true",
                     help="time the streamed instance only (no tables, no other workloads)")

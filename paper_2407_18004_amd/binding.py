@@ -87,6 +87,8 @@ def load_library():
     lib.bcast_schedules_ws.argtypes = [u32, u32, u64, u64, vp, vp, i64, vp, ctypes.c_size_t, vp]
     lib.bcast_schedules_digest_ws.argtypes = [u32, u32, u64, u64, vp, vp, vp, ctypes.c_size_t, vp]
     lib.bcast_schedules_edgecheck_ws.argtypes = [u32, u32, u64, u64, vp, vp, ctypes.c_size_t, vp]
+    lib.bcast_schedules_digest_chunks.argtypes = [u32, u32, u64, u64, u64, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.bcast_schedules_digest_chunks.restype = ctypes.c_int
     for name in ("bcast_schedules_ws", "bcast_schedules_digest_ws", "bcast_schedules_edgecheck_ws"):
         getattr(lib, name).restype = ctypes.c_int
     lib.bcast_baseblocks.argtypes = [u32, vp, vp]
@@ -187,6 +189,18 @@ def bcast_schedules_digest_ws(p: int, root: int, r_begin: int, r_end: int, diges
         _dev_ptr(flags, torch.int32, "flags"), _dev_ptr(workspace, torch.uint8, "workspace"),
         0 if workspace is None else workspace.numel(), _stream_handle(stream)),
         "bcast_schedules_digest_ws")
+
+
+def bcast_schedules_digest_chunks(p: int, root: int, r_begin: int, r_end: int, chunk_ranks: int, digests,
+                                  flags, workspace=None, stream=None) -> None:
+    """digests: device int64 tensor, flags: device int32 tensor, one element per chunk of chunk_ranks
+    ranks; workspace: uint8 tensor of bcast_schedules_workspace(p) bytes, or None."""
+    import torch
+    _check(load_library().bcast_schedules_digest_chunks(
+        p, root, r_begin, r_end, chunk_ranks, _dev_ptr(digests, torch.int64, "digests"),
+        _dev_ptr(flags, torch.int32, "flags"), _dev_ptr(workspace, torch.uint8, "workspace"),
+        0 if workspace is None else workspace.numel(), _stream_handle(stream)),
+        "bcast_schedules_digest_chunks")
 
 
 def bcast_schedules_edgecheck_ws(p: int, root: int, r_begin: int, r_end: int, xors, workspace,

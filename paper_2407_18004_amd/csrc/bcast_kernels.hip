@@ -499,6 +499,9 @@ struct DigestParams {
   RunSplit runs;
   uint64_t *digest;
   uint32_t *flags;
+  // Row (of the launch) >> slot_shift is the place of a rank's hash and flags in digest[] and
+  // flags[] (edge check: digest[2 slot], digest[2 slot + 1]); 63: one place for all ranks.
+  uint32_t slot_shift;
   DeepTable table;                  // kernels with kMemo only
   // Ranks that k_digest<true, ...> leaves to k_digest_listed (row of the launch), or null: then the
   // kernel computes them again itself, 64 at a time.  rank_count: entries claimed so far (may run
@@ -510,8 +513,10 @@ struct DigestParams {
 constexpr uint32_t kNoRank = 0xFFFFFFFFu;            // a slot of the list that no claim that fit covers
 
 // (`count`, or null: the count of the list of ranks, cleared for the kernels that follow)
-__global__ void k_digest_init(uint64_t *digest, uint32_t *flags, uint32_t *count) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) { *digest = 0; *flags = 0; if (count) *count = 0; }
+__global__ void k_digest_init(uint64_t *digest, uint32_t *flags, uint32_t *count, uint64_t n_slots) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_slots) { digest[i] = 0; flags[i] = 0; }
+  if (i == 0 && count) *count = 0;
 }
 
 __global__ void k_edges_init(uint64_t *xors, uint32_t *count) {
@@ -547,8 +552,29 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
   int8_t *send_row = recv_row + q;
   const uint64_t n_tiles = (prm.n_ranks + kWave - 1) / kWave;
 
+  // What the lanes have gathered for the ranks of output slot cur_slot (the same in all lanes)
+  // goes out whenever the wavefront moves on to ranks of another slot, and at the end.
   uint64_t acc = 0, acc2 = 0;
   uint32_t acc_flags = 0;
+  uint32_t cur_slot = 0;
+  auto flush = [&]() {
+    acc = wave_xor64(acc);
+    if (kEdges) acc2 = wave_xor64(acc2);
+    acc_flags = wave_or32(acc_flags);
+    if (lane == 0) {
+      if (kEdges) {
+        atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 2u * (uint64_t)cur_slot), (unsigned long long)acc);
+        atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 2u * (uint64_t)cur_slot + 1u), (unsigned long long)acc2);
+      } else {
+        atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + cur_slot), (unsigned long long)acc);
+        if (acc_flags) atomicOr(prm.flags + cur_slot, acc_flags);
+      }
+    }
+    acc = 0; acc2 = 0; acc_flags = 0;
+  };
+  auto enter_slot = [&](uint32_t slot) {                     // slot: the same in all lanes
+    if (slot != cur_slot) { flush(); cur_slot = slot; }
+  };
   auto take_row = [&](uint32_t r, uint32_t v, int b) {       // the lane's row is complete
     if (kEdges) {
       edge_rank(in, r, recv_row, acc, acc2);
@@ -570,6 +596,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
     for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
       const TileState st = tile_rows<kMemo>(in, prm.r_begin, prm.n_ranks, tile, n_tiles, lds_dyn, slice_w,
                                             pitch, q, lane, wave, record, long_run, prm.table);
+      enter_slot((uint32_t)((tile * kWave) >> prm.slot_shift));
       acc_flags |= st.flags;
       if (lane < st.n_valid) take_row((uint32_t)(prm.r_begin + tile * kWave + lane), st.v, st.b);
       wave_lds_sync();                         // the slice is rewritten next
@@ -605,6 +632,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
       }
       if (!batch && tile == t_lo) break;
       uint64_t row = 0;                        // the lane's rank, as a row of the launch
+      uint64_t row0_of_pass = 0;               // first row of the tile, if the pass is a tile
       uint32_t n_here;                         // lanes with a rank in this pass
       if (batch) {
         n_here = n_queued < (uint32_t)kWave ? n_queued : (uint32_t)kWave;
@@ -614,6 +642,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
         const uint64_t row0 = tile * kWave;
         n_here = prm.n_ranks - row0 < kWave ? (uint32_t)(prm.n_ranks - row0) : kWave;
         row = row0 + lane;
+        row0_of_pass = row0;
       }
       const uint32_t r = (uint32_t)(prm.r_begin + row);
       uint32_t v = 0, viol = 0, flags = 0;
@@ -625,19 +654,34 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
         viol = compute_rank_phase1<kMemo>(in, v, recv_row, send_row, b, flags, record,
                                           !batch && long_run && n_here == (uint32_t)kWave, prm.table, memo);
       }
-      acc_flags |= flags;
       wave_lds_sync();
       uint32_t open = 0;
       if (lane < n_here) {
         if (batch) {                           // no neighbours here: from the table, else by search
           const uint32_t left = kMemo ? resolve_from_table(in, prm.table, v, memo, viol, send_row) : viol;
-          acc_flags |= resolve_by_search(in, v, left, send_row);
+          flags |= resolve_by_search(in, v, left, send_row);
         } else {
           open = resolve_from_tiles(in, viol, send_row, tile_recv, n_valid_above ? above : nullptr,
                                     pitch, kAboveRounds, lane, n_here, n_valid_above);
           if (kMemo) open = resolve_from_table(in, prm.table, v, memo, open, send_row);
         }
-        if (open == 0) take_row(r, v, b);
+      }
+      if (!batch) {                            // a tile lies in one slot
+        enter_slot((uint32_t)(row0_of_pass >> prm.slot_shift));
+        acc_flags |= flags;
+        if (lane < n_here && open == 0) take_row(r, v, b);
+      } else {                                 // ranks from anywhere in the run: slot by slot
+        const uint32_t my_slot = (uint32_t)(row >> prm.slot_shift);
+        bool todo = lane < n_here;
+        for (uint64_t who = __ballot(todo); who != 0; who = __ballot(todo)) {
+          const uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)my_slot, __ffsll((long long)who) - 1);
+          enter_slot(slot);
+          if (todo && my_slot == slot) {
+            acc_flags |= flags;
+            take_row(r, v, b);
+            todo = false;
+          }
+        }
       }
       if (batch) {
         n_queued -= n_here;
@@ -658,14 +702,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kShare ?
       wave_lds_sync();                         // slice and queue are rewritten next
     }
   }
-  acc = wave_xor64(acc);
-  if (kEdges) acc2 = wave_xor64(acc2);
-  acc_flags = wave_or32(acc_flags);
-  if (lane == 0) {
-    atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
-    if (kEdges) atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + 1), (unsigned long long)acc2);
-    else if (acc_flags) atomicOr(prm.flags, acc_flags);
-  }
+  flush();
 }
 
 // The ranks that k_digest<true, ...> put on the list: each lane computes one of them on its own
@@ -689,9 +726,21 @@ __global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
   const uint32_t n = claimed < prm.rank_cap ? claimed : prm.rank_cap;
   uint64_t acc = 0;
   uint32_t acc_flags = 0;
+  uint32_t cur_slot = 0;                       // as in k_digest
+  auto flush = [&]() {
+    acc = wave_xor64(acc);
+    acc_flags = wave_or32(acc_flags);
+    if (lane == 0 && (acc != 0 || acc_flags != 0)) {
+      atomicXor(reinterpret_cast<unsigned long long *>(prm.digest + cur_slot), (unsigned long long)acc);
+      if (acc_flags) atomicOr(prm.flags + cur_slot, acc_flags);
+    }
+    acc = 0; acc_flags = 0;
+  };
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   for (uint32_t i0 = (blockIdx.x * kWavesPerBlock + wave) * kWave; i0 < n; i0 += n_waves * kWave) {
     const uint32_t row = i0 + lane < n ? prm.rank_list[i0 + lane] : kNoRank;
+    uint64_t h = 0;
+    uint32_t fl_row = 0;
     if (row != kNoRank) {
       const uint32_t r = (uint32_t)(prm.r_begin + row);
       const uint32_t v = virtual_rank(in, r);
@@ -705,20 +754,24 @@ __global__ __launch_bounds__(kBlock) void k_digest_listed(DigestParams prm) {
       const uint32_t viol = compute_rank_phase1<false, true>(in, v, recv_row, send_row, b, flags, none, false,
                                                              no_table, unused);
       flags |= resolve_by_search<true>(in, v, viol, send_row);
-      acc_flags |= flags;
-      uint64_t h;
       uint32_t fl2;
       digest_rank(in, r, v, b, recv_row, h, fl2);
-      acc ^= h;
-      acc_flags |= fl2;
+      fl_row = flags | fl2;
+    }
+    // the listed ranks come from anywhere in the range: slot by slot
+    const uint32_t my_slot = row != kNoRank ? (uint32_t)((uint64_t)row >> prm.slot_shift) : 0u;
+    bool todo = row != kNoRank;
+    for (uint64_t who = __ballot(todo); who != 0; who = __ballot(todo)) {
+      const uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)my_slot, __ffsll((long long)who) - 1);
+      if (slot != cur_slot) { flush(); cur_slot = slot; }
+      if (todo && my_slot == slot) {
+        acc ^= h;
+        acc_flags |= fl_row;
+        todo = false;
+      }
     }
   }
-  acc = wave_xor64(acc);
-  acc_flags = wave_or32(acc_flags);
-  if (lane == 0 && (acc != 0 || acc_flags != 0)) {
-    atomicXor(reinterpret_cast<unsigned long long *>(prm.digest), (unsigned long long)acc);
-    if (acc_flags) atomicOr(prm.flags, acc_flags);
-  }
+  flush();
 }
 
 // ------------------------------------------------- table of deep entries
@@ -1584,12 +1637,16 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
 }
 
 // digest and flags (edges = false) or the two sums of the edge check (edges = true, into out64)
+// slot_shift: 63 for one result, else log2 of the ranks per result (digest and flags only).
 int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
-                uint64_t *out64, uint32_t *flags, void *workspace, void *stream) {
+                uint64_t *out64, uint32_t *flags, void *workspace, void *stream,
+                uint32_t slot_shift = 63u) {
   const int q = host_q(p);
-  if (q < 0 || root >= p || r_begin > r_end || r_end > p || !out64 || (!edges && !flags))
-    return BCAST_EINVAL;
+  if (q < 0 || root >= p || r_begin > r_end || r_end > p) return BCAST_EINVAL;
   const uint64_t n = r_end - r_begin;
+  const uint64_t n_slots = slot_shift >= 63u ? 1u : (n + (1ull << slot_shift) - 1u) >> slot_shift;
+  if (n_slots != 0 && (!out64 || (!edges && !flags))) return BCAST_EINVAL;
+  if (n_slots == 0) return BCAST_OK;             // an empty range in chunks: nothing to write
   const bool share = keep_next_tile(p);
   const bool work = n != 0 && !(edges && q == 0);
   int grid = 1;
@@ -1609,13 +1666,15 @@ int digest_impl(bool edges, uint32_t p, uint32_t root, uint64_t r_begin, uint64_
     rank_list = reinterpret_cast<uint32_t *>(base + 256u);
   }
   if (edges) hipLaunchKernelGGL(k_edges_init, dim3(1), dim3(64), 0, st, out64, rank_count);
-  else hipLaunchKernelGGL(k_digest_init, dim3(1), dim3(64), 0, st, out64, flags, rank_count);
+  else hipLaunchKernelGGL(k_digest_init, dim3((unsigned)((n_slots + 63u) / 64u)), dim3(64), 0, st, out64, flags,
+                          rank_count, n_slots);
   if (!launch_ok()) return BCAST_EHIP;
   if (!work) return BCAST_OK;
   DigestParams prm;
   prm.p = p; prm.q = (uint32_t)q; prm.root = root;
   prm.r_begin = r_begin; prm.n_ranks = n;
   prm.digest = out64; prm.flags = edges ? nullptr : flags;
+  prm.slot_shift = slot_shift;
   prm.rank_list = rank_list; prm.rank_count = rank_count;
   prm.rank_cap = rank_list ? open_list_capacity(p) * 2u : 0u;
   prm.runs = split_runs((n + kWave - 1) / kWave, grid);
@@ -1686,6 +1745,21 @@ int bcast_schedules_digest_ws(uint32_t p, uint32_t root, uint64_t r_begin, uint6
   const int rc = check_workspace(p, workspace, workspace_bytes);
   if (rc != BCAST_OK) return rc;
   return digest_impl(false, p, root, r_begin, r_end, digest, flags, workspace, stream);
+}
+
+int bcast_schedules_digest_chunks(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,
+                                  uint64_t chunk_ranks, uint64_t *digests, uint32_t *flags,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  if (chunk_ranks < (uint64_t)kWave || (chunk_ranks & (chunk_ranks - 1u)) != 0 || chunk_ranks > (1ull << 62))
+    return BCAST_EINVAL;
+  uint32_t shift = 0;
+  while ((1ull << shift) < chunk_ranks) ++shift;
+  if (r_begin <= r_end && ((r_end - r_begin + chunk_ranks - 1u) >> shift) > 0xFFFFFFFFull) return BCAST_EINVAL;
+  if (workspace || workspace_bytes != 0) {
+    const int rc = check_workspace(p, workspace, workspace_bytes);
+    if (rc != BCAST_OK) return rc;
+  }
+  return digest_impl(false, p, root, r_begin, r_end, digests, flags, workspace, stream, shift);
 }
 
 int bcast_schedules_edgecheck(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end,

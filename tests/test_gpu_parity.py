@@ -834,6 +834,50 @@ def test_calls_with_workspace_on_the_streamed_instance():
         del t
 
 
+def gpu_digest_chunks(p, root, a, b, chunk, ws=None):
+    n_slots = max(0, -(-(b - a) // chunk))
+    dg = torch.full((n_slots + 1,), -1, dtype=torch.int64, device=DEV)       # one more: must stay as it is
+    fl = torch.full((n_slots + 1,), -1, dtype=torch.int32, device=DEV)
+    lib.bcast_schedules_digest_chunks(p, root, a, b, chunk, dg, fl, ws)
+    torch.cuda.synchronize()
+    d, f = dg.cpu().tolist(), fl.cpu().tolist()
+    assert d[n_slots] == -1 and f[n_slots] == -1
+    return [(x & oracle.U64_MAX, y & 0xFFFFFFFF) for x, y in zip(d[:n_slots], f[:n_slots])]
+
+
+@pytest.mark.parametrize("p,root,a,n,chunk", [
+    (1000003, 5, 0, 1000003, 2**17),           # violations; the last chunk ragged
+    (1000003, 999999, 123, 700000, 64),        # a chunk per tile: batches of deferred ranks mix chunks
+    (2**22 + 1, 7, 1000, 2**22 - 5000, 2**12), # more than one violation per rank; with the workspace: the list of ranks
+    (2**23 - 1, 3, 0, 2**23 - 1, 2**20),       # the kernels whose wavefronts work alone
+    (2**24, 2**23 + 5, 2**23 - 2_000_000, 4_000_001, 2**16),
+    (4099, 0, 0, 4099, 128), (100, 3, 10, 80, 64), (1, 0, 0, 1, 64), (1000, 1, 500, 0, 64),
+])
+def test_digests_of_all_chunks_in_one_call(p, root, a, n, chunk):
+    b = a + n
+    want = [oracle.digest(p, root, lo, min(lo + chunk, b), send_mode=1) for lo in range(a, b, chunk)]
+    assert gpu_digest_chunks(p, root, a, b, chunk) == want
+    ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+    assert gpu_digest_chunks(p, root, a, b, chunk, ws) == want
+    if n:
+        assert gpu_digest_chunks(p, root, a, b, 2**40) == [gpu_digest(p, root, a, b)]      # one chunk
+
+
+def test_workload3_all_chunk_digests_in_one_call():
+    p = workloads.STREAMED_P
+    gold = streamed_golden()
+    ws = torch.empty(lib.bcast_schedules_workspace(p), dtype=torch.uint8, device=DEV)
+    got = gpu_digest_chunks(p, 0, 0, p, workloads.STREAMED_CHUNK, ws)
+    assert [f"{d:016x}" for d, _ in got] == [c["digest"] for c in gold["chunks"]]
+    assert all(f == 0 for _, f in got)
+    with pytest.raises(lib.BcastError):
+        lib.bcast_schedules_digest_chunks(p, 0, 0, p, 100, torch.zeros(1, dtype=torch.int64, device=DEV),
+                                          torch.zeros(1, dtype=torch.int32, device=DEV), None)     # not a power of two
+    with pytest.raises(lib.BcastError):
+        lib.bcast_schedules_digest_chunks(p, 0, 0, p, 32, torch.zeros(1, dtype=torch.int64, device=DEV),
+                                          torch.zeros(1, dtype=torch.int32, device=DEV), None)     # below 64
+
+
 def test_calls_with_workspace_argument_errors():
     p = 4000037
     q = lib.bcast_q(p)

@@ -948,7 +948,7 @@ constexpr uint32_t kLongQueue = 2 * kWave;      // 63 waiting + one more from ev
 
 struct BatchLds {
   uint32_t *rows;                   // kTileBytes of the wavefront's own
-  uint16_t *open_entry;             // 4 * kWave: lane << 5 | k, at most four per rank
+  uint16_t *open_entry;             // kShortRounds * kWave: lane << 5 | k, one per rank and round below kShortRounds
   uint32_t *open_v;                 // kWave: the owner's virtual rank
   uint16_t *waiting;                // kLongQueue
 };
@@ -1056,7 +1056,7 @@ __device__ __forceinline__ bool batch_instance(const BatchParams &prm, uint32_t 
 
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_batched(BatchParams prm) {
   __shared__ __align__(16) uint32_t lds[kWavesPerBlock][kTileBytes / 4];
-  __shared__ uint16_t open_entry[kWavesPerBlock][4 * kWave];
+  __shared__ uint16_t open_entry[kWavesPerBlock][kShortRounds * kWave];
   __shared__ uint32_t open_v[kWavesPerBlock][kWave];
   __shared__ uint16_t waiting[kWavesPerBlock][kLongQueue];
   const uint32_t lane = threadIdx.x & (kWave - 1);
@@ -1624,7 +1624,7 @@ int schedules_impl(uint32_t p, uint32_t root, uint64_t r_begin, uint64_t r_end, 
     if (prm.open_list) {
       if (!launch_ok()) return BCAST_EHIP;
       const uint64_t most = prm.open_segments != 0u ? (uint64_t)prm.open_segments * prm.open_cap
-                            : n * 4u < prm.open_cap ? n * 4u : prm.open_cap;    // at most four per rank
+                            : n * 4u < prm.open_cap ? n * 4u : prm.open_cap;    // (sizes the grid only: its threads stride over the list)
       const uint64_t blocks_fill = (most + kBlock - 1) / kBlock;
       hipLaunchKernelGGL(k_fill_open, dim3((unsigned)(blocks_fill < 2048u ? (blocks_fill ? blocks_fill : 1u) : 2048u)),
                          dim3(kBlock), 0, (hipStream_t)stream, prm);

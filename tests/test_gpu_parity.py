@@ -863,6 +863,18 @@ def test_digests_of_all_chunks_in_one_call(p, root, a, n, chunk):
         assert gpu_digest_chunks(p, root, a, b, 2**40) == [gpu_digest(p, root, a, b)]      # one chunk
 
 
+def test_the_flag_for_more_than_four_violations():
+    # p = 2^30 + 1, r = 3 * 2^26: five violations of Algorithm 6 (see the oracle's pins)
+    p, r = 2**30 + 1, 3 * 2**26
+    for a, b in [(r, r + 1), (r - 1000, r + 1000), (r - 64, r)]:
+        assert gpu_digest(p, 0, a, b) == oracle.digest(p, 0, a, b, send_mode=1), (a, b)
+    assert gpu_digest(p, 0, r - 1000, r + 1000)[1] == 8 and gpu_digest(p, 0, r - 64, r)[1] == 0
+    ws = torch.full((lib.bcast_schedules_workspace(p),), 0xEE, dtype=torch.uint8, device=DEV)
+    got = gpu_digest_chunks(p, 0, r - 2**21, r + 2**21, 2**20, ws)
+    assert got == [oracle.digest(p, 0, lo, lo + 2**20, send_mode=1) for lo in range(r - 2**21, r + 2**21, 2**20)]
+    assert [f for _, f in got] == [0, 0, 8, 0]
+
+
 def test_workload3_all_chunk_digests_in_one_call():
     p = workloads.STREAMED_P
     gold = streamed_golden()

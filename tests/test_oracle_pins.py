@@ -131,6 +131,19 @@ def test_named_violation_p17():
     assert send.tolist() == [-3, -3, -3, -2, -3] and nviol == 1
 
 
+def test_five_violations_beyond_the_sizes_the_paper_checked():
+    # Theorem 3 counts at most four violations per processor, and Section 2.3 reports that bound
+    # as checked for p up to some millions.  At p = 2^30 + 1 Algorithm 6 as written here takes
+    # the violation branch five times for r = 3 * 2^26 (rounds 1, 2, 3, 5 and 27); what it computes
+    # is still the schedule of the definition.  This is what raises BCAST_F_VIOLATIONS on that p.
+    p, r = 2**30 + 1, 3 * 2**26
+    send, nviol, mask = oracle.sendschedule(p, r, with_violations=True)
+    assert nviol == 5 and mask == (1 << 1 | 1 << 2 | 1 << 3 | 1 << 5 | 1 << 27)
+    assert send.tolist() == oracle.sendschedule_def(p, r).tolist()
+    assert oracle.digest(p, 0, r, r + 1, send_mode=1)[1] == 8
+    assert oracle.digest(p, 0, r - 64, r, send_mode=1)[1] == 0
+
+
 # --------------------------------------------- the four conditions --------
 
 def check_conditions(p, S):
